@@ -1,0 +1,157 @@
+/*
+ * oserve.h - C ABI of the MI355X (gfx950) paged GQA decode-attention library.
+ *
+ * The operation: one decode step of attention for a batch of requests whose
+ * context lengths differ widely (short compute-bound requests mixed with long
+ * memory-bound ones: paper section 1 (i) and section 2, "Workload
+ * heterogeneity").  Per section 2, "Phases of LLM inference", a decode step
+ * takes the last generated token and the KV cache as inputs, so each query head
+ * of each request holds ONE query vector that attends over all cached keys and
+ * values of that request; the paper characterises this phase as
+ * memory-bandwidth-bound (section 2; appendix C, "Decoding phase").  The cache
+ * is held in fixed-size blocks (section 5.2, "KV cache transmission"); the
+ * block ("page") size, the pool layout and the block-table format below are
+ * this library's choices, the paper does not fix them.
+ *
+ * For request b, query head h, kv head j = h / (num_q_heads / num_kv_heads),
+ * L = context_lens[b]:
+ *
+ *     k_t = k_pages[block_table[b][t / page_size]][j][t % page_size][:]   t = 0..L-1
+ *     out[b][h][:] = sum_t softmax_t(scale * <q[b][h], k_t>) * v_t
+ *
+ * computed in two kernels on the caller's stream: a split kernel (one
+ * wavefront per (request, kv head, sequence split), online softmax, fp32
+ * accumulation, bf16 MFMA) and a log-sum-exp merge of the splits.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host; `plan`
+ *     objects are host objects owned by the library.
+ *   - The caller owns all device memory, including `workspace`.  Launch calls
+ *     never allocate or free device memory and never synchronise with the
+ *     device, except that a plan used for more than OSERVE_PLAN_RING launches
+ *     without the stream draining blocks on the oldest launch's upload.
+ *   - Every function returns a status code; nothing throws or aborts.
+ *   - hipStream_t is passed as void* (null = the default stream).
+ */
+#ifndef OSERVE_H_
+#define OSERVE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct oserve_plan oserve_plan_t;
+
+typedef enum {
+    OSERVE_OK = 0,
+    OSERVE_ERR_NULL = 1,          /* a required pointer is null */
+    OSERVE_ERR_SHAPE = 2,         /* unsupported head geometry, page size or batch */
+    OSERVE_ERR_CONTEXT_LEN = 3,   /* a context length < 1 or beyond the block-table width */
+    OSERVE_ERR_WORKSPACE = 4,     /* workspace too small or misaligned */
+    OSERVE_ERR_PLAN_MISMATCH = 5, /* batch larger than the plan's capacity, or plan has no device */
+    OSERVE_ERR_DEVICE = 6         /* a HIP runtime call failed */
+} oserve_status_t;
+
+/* Launches a plan may have in flight before a launch call waits for the oldest. */
+#define OSERVE_PLAN_RING 8
+
+/* Supported shapes: head_dim 64 or 128; page_size 16; num_q_heads a multiple of
+ * num_kv_heads with group size num_q_heads / num_kv_heads <= 16. */
+
+/*
+ * Plan: sizes the sequence splits of one batch from its context lengths (the
+ * step that lets short and long requests fill the GPU together).  The
+ * sequence of request b (N_b pages) is cut into S_b = ceil(N_b / C) splits of
+ * ceil(N_b / S_b) pages each, where C (pages) is `split_tokens / page_size`,
+ * or, when `split_tokens` is 0, is chosen so that the batch yields a few work
+ * items per resident wavefront of the device.  Work items (request, kv head,
+ * split) are ordered longest split first.  Host-only, O(batch log batch).
+ *
+ *   context_lens_host  [batch] int32, host memory, each in [1, max_pages_per_seq*page_size]
+ *   max_pages_per_seq  row stride (entries) of the block table passed at launch
+ *   split_tokens       0 = automatic; else a positive multiple of page_size
+ *   device_id          HIP device whose compute-unit count sizes the splits and on
+ *                      which the plan will be launched; -1 = no device (planning
+ *                      only, assumes 256 compute units; such a plan cannot launch)
+ *   capacity           largest batch a later oserve_plan_update may bring (>= batch)
+ *
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_CONTEXT_LEN, OSERVE_ERR_DEVICE.
+ * On error *plan_out is null.
+ */
+oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t batch,
+                                   int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
+                                   int32_t page_size, int32_t max_pages_per_seq,
+                                   int32_t split_tokens, int32_t device_id, int32_t capacity,
+                                   oserve_plan_t** plan_out);
+
+/*
+ * Re-plan in place for the next decode step (context lengths grow by one per
+ * step, section 2 "step-by-step").  No allocation.  batch <= capacity.
+ * On error the plan keeps its previous contents.
+ */
+oserve_status_t oserve_plan_update(oserve_plan_t* plan, const int32_t* context_lens_host,
+                                   int32_t batch);
+
+void oserve_plan_destroy(oserve_plan_t* plan); /* null is allowed; the plan's launches must have completed */
+
+/* Plan queries (plan must be non-null). */
+int32_t oserve_plan_batch(const oserve_plan_t* plan);
+int32_t oserve_plan_num_work_items(const oserve_plan_t* plan); /* grid size of the split kernel */
+int32_t oserve_plan_split_pages(const oserve_plan_t* plan);    /* C, in pages */
+/* Splits of request b: count, pages per split, index of its first work item.  Any out pointer may be null. */
+oserve_status_t oserve_plan_request(const oserve_plan_t* plan, int32_t b, int32_t* num_splits,
+                                    int32_t* pages_per_split, int32_t* first_item);
+/* Bytes of `workspace` the current plan needs, and a bound valid after any update. */
+size_t oserve_plan_workspace_bytes(const oserve_plan_t* plan);
+size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);
+
+/*
+ * One decode step of paged attention (definition at the top of this file).
+ * Enqueues on `stream`: a small upload of the plan's per-request records into
+ * `workspace`, the split kernel, and the merge kernel.  Returns without
+ * waiting.
+ *
+ *   workspace      device, >= oserve_plan_workspace_bytes(plan), 256-byte aligned;
+ *                  contents are scratch.  Two launches that overlap in time must
+ *                  not share a workspace.
+ *   q              bf16 [batch, num_q_heads, head_dim], contiguous
+ *   k_pages        bf16 [num_pages, num_kv_heads, page_size, head_dim], contiguous,
+ *   v_pages        same shape; 16-byte aligned.  Slots at or beyond a request's
+ *                  context length, and pages no table row names, are never read.
+ *   block_table    int32 [batch, max_pages_per_seq]: physical page of logical page p of
+ *                  request b.  Only the first ceil(L_b / page_size) entries of a row are read.
+ *   context_lens   int32 [batch], the device copy of the lengths the plan was built from.
+ *                  A device value that disagrees with the plan is clamped into the last
+ *                  planned page of the request (no out-of-range read results).
+ *   scale          multiplies the fp32 score q.k (not q)
+ *   out            fp32 [batch, num_q_heads, head_dim], contiguous
+ *
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_WORKSPACE, OSERVE_ERR_PLAN_MISMATCH,
+ * OSERVE_ERR_DEVICE.  Not checkable without a device round trip, hence undefined
+ * behaviour: block-table entries outside the pool.
+ */
+oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
+                                         size_t workspace_bytes, const void* q,
+                                         const void* k_pages, const void* v_pages,
+                                         const int32_t* block_table, const int32_t* context_lens,
+                                         float scale, float* out, void* stream);
+
+/*
+ * Optional timing of the split kernel alone.  When enabled, each launch
+ * brackets the split kernel with HIP events on the launch stream.
+ * oserve_plan_split_kernel_ms waits for the launches recorded so far and
+ * returns the mean split-kernel duration in milliseconds over all launches
+ * since timing was enabled (enabling again resets the mean), and their count.
+ */
+oserve_status_t oserve_plan_enable_timing(oserve_plan_t* plan, int32_t enable);
+oserve_status_t oserve_plan_split_kernel_ms(oserve_plan_t* plan, float* mean_ms, int32_t* count);
+
+const char* oserve_status_string(oserve_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSERVE_H_ */

@@ -1,0 +1,192 @@
+"""Thin ctypes binding over the C ABI in include/oserve.h (argument marshalling only).
+
+Every step of the path runs in the library's kernels; torch is used for device
+memory and the stream handle.  There is no fallback: if the built library is
+missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liboserve.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_CONTEXT_LEN, ERR_WORKSPACE, ERR_PLAN_MISMATCH, ERR_DEVICE = range(7)
+PLAN_RING = 8
+
+
+class OserveError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2602_12151_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32, vp, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    pi32 = ctypes.POINTER(ctypes.c_int32)
+    lib.oserve_plan_create.restype = ctypes.c_int
+    lib.oserve_plan_create.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, ctypes.POINTER(vp)]
+    lib.oserve_plan_update.restype = ctypes.c_int
+    lib.oserve_plan_update.argtypes = [vp, vp, i32]
+    lib.oserve_plan_destroy.restype = None
+    lib.oserve_plan_destroy.argtypes = [vp]
+    for name in ("oserve_plan_batch", "oserve_plan_num_work_items", "oserve_plan_split_pages"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp]
+    lib.oserve_plan_request.restype = ctypes.c_int
+    lib.oserve_plan_request.argtypes = [vp, i32, pi32, pi32, pi32]
+    for name in ("oserve_plan_workspace_bytes", "oserve_plan_workspace_bytes_max"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [vp]
+    lib.oserve_paged_decode_attn.restype = ctypes.c_int
+    lib.oserve_paged_decode_attn.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_plan_enable_timing.restype = ctypes.c_int
+    lib.oserve_plan_enable_timing.argtypes = [vp, i32]
+    lib.oserve_plan_split_kernel_ms.restype = ctypes.c_int
+    lib.oserve_plan_split_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
+    lib.oserve_status_string.restype = ctypes.c_char_p
+    lib.oserve_status_string.argtypes = [ctypes.c_int]
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.oserve_status_string(status).decode()
+
+
+def _host_lens(context_lens_host) -> np.ndarray:
+    a = np.ascontiguousarray(np.asarray(context_lens_host), dtype=np.int32)
+    if a.ndim != 1:
+        raise ValueError("context_lens_host must be 1-D")
+    return a
+
+
+class Plan:
+    """Owns an oserve_plan_t*.  Mirrors oserve_plan_* one to one."""
+
+    def __init__(self, context_lens_host, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                 page_size: int, max_pages_per_seq: int, split_tokens: int = 0,
+                 device_id: int = 0, capacity: int | None = None):
+        lens = _host_lens(context_lens_host)
+        self._h = ctypes.c_void_p()
+        st = lib.oserve_plan_create(lens.ctypes.data, len(lens), num_q_heads, num_kv_heads, head_dim,
+                                    page_size, max_pages_per_seq, split_tokens, device_id,
+                                    len(lens) if capacity is None else capacity, ctypes.byref(self._h))
+        if st != OK:
+            self._h = ctypes.c_void_p()
+            raise OserveError(st, "oserve_plan_create")
+
+    def update(self, context_lens_host) -> None:
+        lens = _host_lens(context_lens_host)
+        st = lib.oserve_plan_update(self._h, lens.ctypes.data, len(lens))
+        if st != OK:
+            raise OserveError(st, "oserve_plan_update")
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) and self._h.value and lib is not None:
+            lib.oserve_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = destroy
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def batch(self) -> int:
+        return lib.oserve_plan_batch(self._h)
+
+    @property
+    def num_work_items(self) -> int:
+        return lib.oserve_plan_num_work_items(self._h)
+
+    @property
+    def split_pages(self) -> int:
+        return lib.oserve_plan_split_pages(self._h)
+
+    @property
+    def workspace_bytes(self) -> int:
+        return lib.oserve_plan_workspace_bytes(self._h)
+
+    @property
+    def workspace_bytes_max(self) -> int:
+        return lib.oserve_plan_workspace_bytes_max(self._h)
+
+    def request(self, b: int):
+        """(num_splits, pages_per_split, first_item) of request b."""
+        s, p, f = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        st = lib.oserve_plan_request(self._h, b, ctypes.byref(s), ctypes.byref(p), ctypes.byref(f))
+        if st != OK:
+            raise OserveError(st, "oserve_plan_request")
+        return s.value, p.value, f.value
+
+    def enable_timing(self, enable: bool = True) -> None:
+        st = lib.oserve_plan_enable_timing(self._h, int(enable))
+        if st != OK:
+            raise OserveError(st, "oserve_plan_enable_timing")
+
+    def split_kernel_ms(self):
+        """(mean ms of the split kernel, launches averaged) since timing was enabled."""
+        ms, n = ctypes.c_float(), ctypes.c_int32()
+        st = lib.oserve_plan_split_kernel_ms(self._h, ctypes.byref(ms), ctypes.byref(n))
+        if st != OK:
+            raise OserveError(st, "oserve_plan_split_kernel_ms")
+        return ms.value, n.value
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def paged_decode_attn(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pages: torch.Tensor,
+                      v_pages: torch.Tensor, block_table: torch.Tensor, context_lens: torch.Tensor,
+                      scale: float, out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_decode_attn on torch tensors (layout checks only; no arithmetic here)."""
+    if not (q.is_cuda and k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda
+            and context_lens.is_cuda and out.is_cuda and workspace.is_cuda):
+        raise ValueError("all tensors must be device tensors")
+    if q.dtype != torch.bfloat16 or k_pages.dtype != torch.bfloat16 or v_pages.dtype != torch.bfloat16:
+        raise TypeError("q / k_pages / v_pages must be bf16")
+    if block_table.dtype != torch.int32 or context_lens.dtype != torch.int32 or out.dtype != torch.float32:
+        raise TypeError("block_table / context_lens must be int32 and out fp32")
+    for t in (q, k_pages, v_pages, block_table, context_lens, out, workspace):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    if k_pages.shape != v_pages.shape or out.shape != q.shape or block_table.shape[0] != q.shape[0]:
+        raise ValueError("shape mismatch")
+    s = torch.cuda.current_stream(q.device) if stream is None else stream
+    st = lib.oserve_paged_decode_attn(plan.handle, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                      _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
+                                      ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_paged_decode_attn")
+    return out
+
+
+class DecodeAttention:
+    """Convenience holder: one plan + a workspace sized for any update, reused every step."""
+
+    def __init__(self, inputs, split_tokens: int = 0, capacity: int | None = None):
+        w = inputs.workload
+        dev = inputs.q.device
+        self.plan = Plan(inputs.context_lens_host, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
+                         inputs.block_table.shape[1], split_tokens, dev.index or 0, capacity)
+        self.workspace = torch.empty(self.plan.workspace_bytes_max, dtype=torch.uint8, device=dev)
+        self.out = torch.empty(inputs.q.shape, dtype=torch.float32, device=dev)
+
+    def step(self, inputs, replan: bool = True) -> torch.Tensor:
+        if replan:
+            self.plan.update(inputs.context_lens_host)
+        return paged_decode_attn(self.plan, self.workspace, inputs.q, inputs.k_pages, inputs.v_pages,
+                                 inputs.block_table, inputs.context_lens, inputs.scale, self.out)

@@ -1,0 +1,334 @@
+// gfx950 kernels: split-sequence paged GQA decode attention + log-sum-exp merge.
+//
+// What is computed is the decode-phase attention of paper section 2 ("Phases
+// of LLM inference": one query vector per head over the whole KV cache of the
+// request; memory-bandwidth-bound) over a cache held in fixed-size blocks
+// (section 5.2).  How it is computed is this library's design for CDNA4:
+//
+//  * one wavefront per work item (request, kv head, sequence split); all
+//    query heads of the GQA group ride in one MFMA tile, so every K/V byte is
+//    fetched once per group;
+//  * K and V pages (16 tokens) go from HBM straight into the register layout
+//    the bf16 MFMA wants, 16 bytes per lane per load, no LDS staging:
+//      S^T[token][head] = K_page[16 x D] * Q^T[D x 16]      (16x16x32 MFMA, D/32 per page)
+//      O^T[dim][head]  += V_page^T[D x 16] * P^T[16 x head]  (16x16x16 MFMA, D/16 per page)
+//    The result layout of the first product (lane = head + 16*(token/4), four
+//    tokens per lane) is exactly the operand layout of the second, so the
+//    probabilities never cross lanes, and every per-head softmax quantity
+//    (running max, normaliser, rescale factor) is lane-local in both;
+//  * P is fed to the MFMA as hi + lo bf16 halves (two accumulations) so the
+//    product keeps ~16 mantissa bits of P; accumulation is fp32;
+//  * NBUF pages of K and V are in flight per wavefront (register ring),
+//    physical page ids come from scalar loads one step ahead.
+//
+// MFMA operand layouts used (wave64, lane = 16*g + i, i = lane % 16):
+//   16x16x32 bf16: A[i][8g..8g+7], B[8g..8g+7][i] as 8 bf16 per lane; D[4g+r][i] as 4 floats.
+//   16x16x16 bf16: A[i][4g..4g+3], B[4g..4g+3][i] as 4 bf16 per lane; D[4g+r][i] as 4 floats.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "kernels.h"
+
+namespace oserve {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// round-to-nearest-even fp32 -> bf16 bit pattern in the low half (inputs are finite and >= 0 here)
+__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int D, int NBUF>
+__global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParams p) {
+    constexpr int KK = D / 32;  // K fragments (16 B) per lane per page = QK MFMAs per page
+    constexpr int EV = D / 16;  // V elements per lane per token = PV MFMA tiles per page
+    constexpr int VW = EV / 2;  // 32-bit words of V per lane per token
+    constexpr int PAGE = 16;
+
+    const int lane = threadIdx.x;
+    const int i16 = lane & 15;  // MFMA row/column index: token (K operand), head (results), dim slot (V operand)
+    const int g4 = lane >> 4;   // MFMA k-group
+    const int item = blockIdx.x;
+
+    // ---- which (request, kv head, split) is this wavefront's item ----
+    int lo = 0, hi = p.batch;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (p.records[mid].first_item <= item) lo = mid; else hi = mid;
+    }
+    const RequestRecord rec = p.records[lo];
+    const int local = item - rec.first_item;
+    const int split = local / p.num_kv_heads;
+    const int kvh = local - split * p.num_kv_heads;
+    const int b = rec.request;
+    const int pbeg = split * rec.pages_per_split;
+    const int pend = min(rec.num_pages, pbeg + rec.pages_per_split);
+    int L = p.context_lens[b];
+    L = min(max(L, (rec.num_pages - 1) * PAGE + 1), rec.num_pages * PAGE);
+
+    // ---- Q as the B operand of the score MFMA: column = head i16, k-slots = dims ----
+    bf16x8 qf[KK];
+    {
+        const bool head_ok = i16 < p.group;
+        const uint16_t* qrow = p.q + (static_cast<int64_t>(b) * p.num_q_heads + kvh * p.group + (head_ok ? i16 : 0)) * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            uint4 w = *reinterpret_cast<const uint4*>(qrow + (4 * kk + g4) * 8);
+            if (!head_ok) w = make_uint4(0u, 0u, 0u, 0u);
+            qf[kk] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    // ---- physical page ids: wave-uniform (scalar) loads, fetched one step before they are needed ----
+    const int32_t* bt_row = p.block_table + static_cast<int64_t>(b) * p.max_pages_per_seq;
+    const int last_page = pend - 1;
+    auto page_id_of = [&](int pg) -> int {  // clamped: never reads a table entry the request does not own
+        return __builtin_amdgcn_readfirstlane(bt_row[min(pg, last_page)]);
+    };
+
+    const int64_t page_elems = static_cast<int64_t>(p.num_kv_heads) * PAGE * D;
+    const int64_t head_off = static_cast<int64_t>(kvh) * PAGE * D;
+    const int k_lane_off = i16 * D + g4 * 8;         // + 32*kk elements
+    const int v_lane_off = (4 * g4) * D + EV * i16;  // + c*D elements
+
+    uint4 kbuf[NBUF][KK];
+    uint32_t vbuf[NBUF][4][VW];
+
+    auto issue = [&](int slot, int pid) {
+        const int64_t base = static_cast<int64_t>(pid) * page_elems + head_off;
+        const uint16_t* kp = p.k_pages + base + k_lane_off;
+        const uint16_t* vp = p.v_pages + base + v_lane_off;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kbuf[slot][kk] = *reinterpret_cast<const uint4*>(kp + 32 * kk);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if constexpr (VW == 4) {
+                const uint4 w = *reinterpret_cast<const uint4*>(vp + c * D);
+                vbuf[slot][c][0] = w.x; vbuf[slot][c][1] = w.y; vbuf[slot][c][2] = w.z; vbuf[slot][c][3] = w.w;
+            } else {
+                const uint2 w = *reinterpret_cast<const uint2*>(vp + c * D);
+                vbuf[slot][c][0] = w.x; vbuf[slot][c][1] = w.y;
+            }
+        }
+    };
+
+    f32x4 acc[EV];
+#pragma unroll
+    for (int e = 0; e < EV; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY;  // running max of (score * scale * log2 e) for head i16
+    float l = 0.f;        // this lane's share of the normaliser (its 4 tokens per page)
+
+    auto consume = [&](int slot, int pg) {
+        // scores: S^T[token 4*g4+r][head i16]
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbuf[slot][kk]), qf[kk], s, 0, 0, 0);
+        float x[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = s[r] * p.scale_log2e;
+
+        const int valid = L - pg * PAGE;  // tokens of this page inside the context (uniform)
+        if (valid < PAGE) {
+            // ragged last page: mask by select (the slots may hold anything, NaN included)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool ok = 4 * g4 + r < valid;
+                x[r] = ok ? x[r] : -INFINITY;
+#pragma unroll
+                for (int w = 0; w < VW; ++w) vbuf[slot][r][w] = ok ? vbuf[slot][r][w] : 0u;
+            }
+        }
+
+        float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        mx = fmaxf(mx, wave_xor_f32(mx, 16));
+        mx = fmaxf(mx, wave_xor_f32(mx, 32));
+        if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {  // some head's max moved: rescale (rare after the first pages)
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+#pragma unroll
+            for (int e = 0; e < EV; ++e) acc[e] *= alpha;
+            m = m_new;
+        }
+        float pr[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pr[r] = __builtin_amdgcn_exp2f(x[r] - m);
+        l += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+
+        // P^T as the B operand (k = token 4*g4+r, column = head): hi and lo bf16 halves
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            hi[r] = bf16_bits_rne(pr[r]);
+            lo[r] = bf16_bits_rne(pr[r] - __uint_as_float(hi[r] << 16));
+        }
+        const uint2 ph = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+        const uint2 pl = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        const short4v p_hi = __builtin_bit_cast(short4v, ph);
+        const short4v p_lo = __builtin_bit_cast(short4v, pl);
+
+        // V^T as the A operand: row = dim slot i16 (dim EV*i16+e), k = token 4*g4+c
+#pragma unroll
+        for (int e = 0; e < EV; ++e) {
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            const uint2 vt = make_uint2(__builtin_amdgcn_perm(vbuf[slot][1][e >> 1], vbuf[slot][0][e >> 1], sel),
+                                        __builtin_amdgcn_perm(vbuf[slot][3][e >> 1], vbuf[slot][2][e >> 1], sel));
+            const short4v a = __builtin_bit_cast(short4v, vt);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, p_hi, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, p_lo, acc[e], 0, 0, 0);
+        }
+    };
+
+    // ---- pipeline: NBUF-1 pages in flight ahead of the one being consumed ----
+    // Steady state issues the loads of page pg+NBUF-1 unconditionally before consuming page pg, so
+    // the only wait is for the oldest page; the last NBUF-1 pages are drained without new loads.
+    // An item shorter than NBUF-1 pages re-loads its last page in the prologue (harmless).
+    int pid_ring[NBUF];
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) pid_ring[u] = page_id_of(pbeg + u);
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) issue(u, pid_ring[u]);
+    int next_pid = pid_ring[NBUF - 1];
+
+    auto drain = [&](int slot, int pg) {
+#pragma unroll
+        for (int k = 0; k < NBUF - 1; ++k)
+            if (pg + k < pend) consume((slot + k) % NBUF, pg + k);
+    };
+
+    const int main_end = pend - (NBUF - 1);
+    int pg = pbeg;
+    bool more = true;
+    while (more) {
+#pragma unroll
+        for (int u = 0; u < NBUF; ++u) {
+            if (more) {
+                if (pg < main_end) {
+                    issue((u + NBUF - 1) % NBUF, next_pid);
+                    next_pid = page_id_of(pg + NBUF);
+                    consume(u, pg);
+                    ++pg;
+                } else {
+                    drain(u, pg);
+                    more = false;
+                }
+            }
+        }
+    }
+
+    // ---- write out: lane holds head i16, dims [4*EV*g4, 4*EV*(g4+1)) ----
+    float l_tot = l + wave_xor_f32(l, 16);
+    l_tot += wave_xor_f32(l_tot, 32);
+    if (i16 < p.group) {
+        const int h = kvh * p.group + i16;
+        float* dst;
+        float mul = 1.f;
+        if (rec.num_splits == 1) {
+            dst = p.out + (static_cast<int64_t>(b) * p.num_q_heads + h) * D;
+            mul = 1.f / l_tot;
+        } else {
+            const int64_t row = static_cast<int64_t>(item) * p.group + i16;
+            dst = p.partial_o + row * D;
+            if (g4 == 0) {
+                p.partial_ml[row * 2] = m;
+                p.partial_ml[row * 2 + 1] = l_tot;
+            }
+        }
+        dst += 4 * EV * g4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+            for (int e4 = 0; e4 < EV / 4; ++e4) {
+                float4 o;
+                o.x = acc[4 * e4 + 0][r] * mul;
+                o.y = acc[4 * e4 + 1][r] * mul;
+                o.z = acc[4 * e4 + 2][r] * mul;
+                o.w = acc[4 * e4 + 3][r] * mul;
+                *reinterpret_cast<float4*>(dst + r * EV + 4 * e4) = o;
+            }
+        }
+    }
+}
+
+// One wavefront per (request, query head) with more than one split:
+//   m* = max_s m_s ; w_s = 2^(m_s - m*) ; out = sum_s w_s o_s / sum_s w_s l_s
+// Splits are combined in index order, so the result is bit-reproducible.
+template <int D>
+__global__ __launch_bounds__(64) void paged_decode_merge_kernel(const MergeParams p) {
+    constexpr int DPL = D / 64;  // dims per lane
+    const int lane = threadIdx.x;
+    const int pos = blockIdx.x / p.num_q_heads;
+    const int h = blockIdx.x - pos * p.num_q_heads;
+    const RequestRecord rec = p.records[pos];
+    const int S = rec.num_splits;
+    if (S == 1) return;  // the split kernel already wrote `out`
+    const int kvh = h / p.group;
+    const int gi = h - kvh * p.group;
+    // row of split s: (first_item + s*Hkv + kvh) * group + gi
+    const int64_t row0 = (static_cast<int64_t>(rec.first_item) + kvh) * p.group + gi;
+    const int64_t row_step = static_cast<int64_t>(p.num_kv_heads) * p.group;
+
+    float mmax = -INFINITY;
+    for (int s = lane; s < S; s += 64) mmax = fmaxf(mmax, p.partial_ml[(row0 + s * row_step) * 2]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mmax = fmaxf(mmax, wave_xor_f32(mmax, off));
+
+    float num[DPL];
+#pragma unroll
+    for (int d = 0; d < DPL; ++d) num[d] = 0.f;
+    float den = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const int64_t row = row0 + s * row_step;
+        const float w = __builtin_amdgcn_exp2f(p.partial_ml[row * 2] - mmax);
+        den += w * p.partial_ml[row * 2 + 1];
+        const float* o = p.partial_o + row * D + lane * DPL;
+        if constexpr (DPL == 2) {
+            const float2 v = *reinterpret_cast<const float2*>(o);
+            num[0] += w * v.x;
+            num[1] += w * v.y;
+        } else {
+            num[0] += w * o[0];
+        }
+    }
+    float* dst = p.out + (static_cast<int64_t>(rec.request) * p.num_q_heads + h) * D + lane * DPL;
+    const float inv = 1.f / den;
+#pragma unroll
+    for (int d = 0; d < DPL; ++d) dst[d] = num[d] * inv;
+}
+
+constexpr int kNumBuf = 3;
+
+}  // namespace
+
+hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipStream_t stream) {
+    if (num_items <= 0) return hipSuccess;
+    if (head_dim == 128)
+        hipLaunchKernelGGL((paged_decode_split_kernel<128, kNumBuf>), dim3(num_items), dim3(64), 0, stream, p);
+    else if (head_dim == 64)
+        hipLaunchKernelGGL((paged_decode_split_kernel<64, kNumBuf>), dim3(num_items), dim3(64), 0, stream, p);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream) {
+    const int grid = batch * p.num_q_heads;
+    if (grid <= 0) return hipSuccess;
+    if (head_dim == 128)
+        hipLaunchKernelGGL((paged_decode_merge_kernel<128>), dim3(grid), dim3(64), 0, stream, p);
+    else if (head_dim == 64)
+        hipLaunchKernelGGL((paged_decode_merge_kernel<64>), dim3(grid), dim3(64), 0, stream, p);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace oserve

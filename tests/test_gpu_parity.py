@@ -1,0 +1,192 @@
+"""GPU-vs-oracle parity of the HIP path, called through the C ABI.
+
+Bar: max-abs error <= 1e-2 and relative L2 error <= 2e-3 against the fp64
+oracle on the same seeded bits (bf16 inputs, fp32 accumulation); bit-exact
+where the mathematics says the GPU result cannot change (page permutation,
+run-to-run).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_12151_amd import workloads as wl
+from tests import gpu_helpers as gh
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(widx, lens, seed=None, **kw):
+    w = wl.WORKLOADS[widx]
+    cpu = wl.make_inputs(w, device="cpu", seed=seed, lens=np.asarray(lens, dtype=np.int32), **kw)
+    return cpu, gh.to_device(cpu)
+
+
+def test_tiny_workload_full():
+    """Workload 0 exactly: lens 17/64/200/513, 8q/2kv, D=64, 64-page permuted pool."""
+    cpu = wl.make_inputs(wl.WORKLOADS[0], device="cpu")
+    dev = gh.to_device(cpu)
+    out, op = gh.gpu_attention(dev)
+    print("tiny:", gh.assert_parity(out, gh.oracle_attention(cpu), "tiny"), "items", op.plan.num_work_items)
+
+
+@pytest.mark.parametrize("split_tokens", [0, 16, 32, 64, 256])
+def test_tiny_workload_all_split_sizes(split_tokens):
+    cpu = wl.make_inputs(wl.WORKLOADS[0], device="cpu")
+    dev = gh.to_device(cpu)
+    out, _ = gh.gpu_attention(dev, split_tokens=split_tokens)
+    gh.assert_parity(out, gh.oracle_attention(cpu), f"tiny split={split_tokens}")
+
+
+@pytest.mark.parametrize("widx", [1, 2, 3])
+def test_boundary_lengths(widx):
+    """Context lengths at page and split boundaries, D=128, group 4 and 8."""
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 127, 128, 129, 255, 256, 257, 1000, 1023, 1024, 1025, 48, 3]
+    cpu, dev = _case(widx, lens, seed=100 + widx)
+    ref = gh.oracle_attention(cpu)
+    for split_tokens in (0, 16, 48, 128, 1024):
+        out, _ = gh.gpu_attention(dev, split_tokens=split_tokens)
+        gh.assert_parity(out, ref, f"w{widx} split={split_tokens}")
+
+
+def test_llama8b_workload_full_size_full_compare():
+    """Workload 1 at full size (batch 64, lens U[128, 2048]); the oracle does all of it in seconds."""
+    cpu = wl.make_inputs(wl.WORKLOADS[1], device="cpu")
+    dev = gh.to_device(cpu)
+    out, op = gh.gpu_attention(dev)
+    e = gh.assert_parity(out, gh.oracle_attention(cpu), "w1")
+    print("w1:", e, "items", op.plan.num_work_items, "split pages", op.plan.split_pages)
+
+
+def test_single_split_path_writes_out_directly():
+    """split_tokens larger than every context: no request is split, the merge kernel is not launched."""
+    lens = [5, 300, 77, 1024]
+    cpu, dev = _case(1, lens, seed=7)
+    out, op = gh.gpu_attention(dev, split_tokens=2048)
+    assert op.plan.num_work_items == len(lens) * 8
+    gh.assert_parity(out, gh.oracle_attention(cpu), "single split")
+
+
+def test_mha_and_group_sizes():
+    """Group sizes 1 (MHA), 2, 8, 16 at D=128 and 64."""
+    for hq, hkv, d in [(4, 4, 128), (8, 4, 128), (16, 2, 128), (16, 1, 128), (4, 4, 64), (16, 1, 64)]:
+        w = wl.Workload(9, "shape", batch=3, num_q_heads=hq, num_kv_heads=hkv, head_dim=d)
+        cpu = wl.make_inputs(w, device="cpu", seed=hq * 100 + hkv, lens=np.array([33, 700, 129], dtype=np.int32))
+        dev = gh.to_device(cpu)
+        out, _ = gh.gpu_attention(dev, split_tokens=128)
+        gh.assert_parity(out, gh.oracle_attention(cpu), f"hq={hq} hkv={hkv} d={d}")
+
+
+def test_unread_memory_is_poisoned_with_nan():
+    """NaN in tail slots of last pages and in every page no table row names must not reach the output."""
+    lens = [1, 15, 17, 100, 513, 1030]
+    cpu, dev = _case(3, lens, seed=11)
+    clean, _ = gh.gpu_attention(dev, split_tokens=64)
+    pk, pv = dev.k_pages.clone(), dev.v_pages.clone()
+    used = torch.zeros(pk.shape[0], dtype=torch.bool, device="cuda")
+    used[torch.from_numpy(cpu.used_pages).cuda()] = True
+    pk[~used] = float("nan")
+    pv[~used] = float("nan")
+    bt = cpu.block_table.numpy()
+    for b, L in enumerate(lens):
+        if L % 16:
+            last = int(bt[b, (L - 1) // 16])
+            pk[last, :, L % 16:, :] = float("nan")
+            pv[last, :, L % 16:, :] = float("nan")
+    poisoned = wl.Inputs(workload=dev.workload, q=dev.q, k_pages=pk, v_pages=pv, block_table=dev.block_table,
+                         context_lens=dev.context_lens, context_lens_host=dev.context_lens_host,
+                         scale=dev.scale, used_pages=dev.used_pages)
+    out, _ = gh.gpu_attention(poisoned, split_tokens=64)
+    assert torch.equal(out, clean)
+    gh.assert_parity(out, gh.oracle_attention(cpu), "poisoned")
+
+
+def test_page_permutation_and_reruns_are_bit_identical():
+    lens = [700, 33, 2000, 16]
+    w = wl.WORKLOADS[1]
+    a_cpu = wl.make_inputs(w, device="cpu", seed=21, lens=np.asarray(lens, dtype=np.int32))
+    a = gh.to_device(a_cpu)
+    out_a, op = gh.gpu_attention(a, split_tokens=256)
+    again = op.step(a).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, again)
+    # move every used page to another physical slot, consistently with the table
+    npool = a.k_pages.shape[0]
+    perm = torch.from_numpy(wl.CounterRng(5).permutation(npool)).cuda()      # new_id = perm[old_id]
+    k2 = torch.empty_like(a.k_pages)
+    v2 = torch.empty_like(a.v_pages)
+    k2[perm] = a.k_pages
+    v2[perm] = a.v_pages
+    bt2 = a.block_table.clone()
+    mask = bt2 >= 0
+    bt2[mask] = perm[bt2[mask].long()].int()
+    b = wl.Inputs(workload=w, q=a.q, k_pages=k2, v_pages=v2, block_table=bt2, context_lens=a.context_lens,
+                  context_lens_host=a.context_lens_host, scale=a.scale, used_pages=None)
+    out_b, _ = gh.gpu_attention(b, split_tokens=256)
+    assert torch.equal(out_a, out_b)
+
+
+def test_large_scores_do_not_overflow():
+    """|score| up to ~100: the running-max subtraction must be in place."""
+    lens = [300, 40]
+    cpu, dev = _case(1, lens, seed=31)
+    cpu.q.mul_(6.0)
+    cpu.k_pages.mul_(1.5)
+    dev = gh.to_device(cpu)
+    ref = gh.oracle_attention(cpu)
+    out, _ = gh.gpu_attention(dev, split_tokens=64)
+    gh.assert_parity(out, ref, "large scores")
+
+
+def test_page_ids_beyond_4gib_offsets():
+    """Physical page ids >= 2^17 put byte offsets past 4 GiB (32 KiB per page): needs 64-bit addressing."""
+    w = wl.WORKLOADS[1]
+    lens = np.array([600, 50, 1500], dtype=np.int32)
+    npool = (1 << 17) + 4096
+    dev = wl.make_inputs(w, device="cuda", seed=41, lens=lens, fill_unused=False, pool_pages_override=npool)
+    assert int(dev.block_table.max()) >= (1 << 17)
+    out, _ = gh.gpu_attention(dev, split_tokens=128)
+    pairs = [(b, h) for b in range(3) for h in (0, 13, 31)]
+    ref = gh.sampled_oracle_rows(dev, pairs)
+    got = torch.stack([out[b, h] for b, h in pairs])
+    gh.assert_parity(got, ref, "big ids")
+
+
+def test_plan_update_between_steps():
+    """One plan object re-planned for a different batch (the per-step serving loop)."""
+    from paper_2602_12151_amd import binding
+    w = wl.WORKLOADS[1]
+    a_cpu = wl.make_inputs(w, device="cpu", seed=51, lens=np.array([100, 900, 17, 2048], dtype=np.int32))
+    b_cpu = wl.make_inputs(w, device="cpu", seed=52, lens=np.array([2000, 31], dtype=np.int32))
+    a, b = gh.to_device(a_cpu), gh.to_device(b_cpu)
+    width = max(a.block_table.shape[1], b.block_table.shape[1])
+
+    def widen(x):
+        bt = torch.full((x.block_table.shape[0], width), -1, dtype=torch.int32, device="cuda")
+        bt[:, : x.block_table.shape[1]] = x.block_table
+        x.block_table = bt
+        return x
+    a, b = widen(a), widen(b)
+    plan = binding.Plan(a.context_lens_host, 32, 8, 128, 16, width, 0, 0, capacity=4)
+    ws = torch.empty(plan.workspace_bytes_max, dtype=torch.uint8, device="cuda")
+    for inp, cpu in ((a, a_cpu), (b, b_cpu), (a, a_cpu)):
+        plan.update(inp.context_lens_host)
+        assert plan.workspace_bytes <= plan.workspace_bytes_max
+        out = torch.empty(inp.q.shape, dtype=torch.float32, device="cuda")
+        binding.paged_decode_attn(plan, ws, inp.q, inp.k_pages, inp.v_pages, inp.block_table,
+                                  inp.context_lens, inp.scale, out)
+        torch.cuda.synchronize()
+        gh.assert_parity(out, gh.oracle_attention(cpu), "update")
+    with pytest.raises(binding.OserveError):
+        plan.update(np.ones(5, dtype=np.int32))        # beyond capacity
+
+
+def test_many_launches_wrap_the_staging_ring():
+    cpu, dev = _case(1, [300, 1200, 64], seed=61)
+    from paper_2602_12151_amd import binding
+    op = binding.DecodeAttention(dev, split_tokens=128)
+    first = op.step(dev).clone()
+    for _ in range(3 * binding.PLAN_RING):
+        out = op.step(dev)
+    torch.cuda.synchronize()
+    assert torch.equal(out, first)
+    gh.assert_parity(out, gh.oracle_attention(cpu), "ring")
