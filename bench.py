@@ -33,6 +33,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default: the heterogeneous mix)")
     ap.add_argument("--split-tokens", type=int, default=0, help="0 = automatic split sizing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
+                    help="instead of the benchmark, run a plain device copy of BYTES bytes --steps times "
+                         "(the known-size kernel that hardware byte counters are scaled by)")
     ap.add_argument("--cpu-token-heads", type=float, default=120e6,
                     help="size of the oracle's sample in (token, query head) pairs")
     return ap.parse_args()
@@ -97,6 +100,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "launches": args.steps}))
+        return
     w = wl.WORKLOADS[args.config]
     sets, nbytes = build_inputs(w, wl, torch)
     ops = [binding.DecodeAttention(s, split_tokens=args.split_tokens) for s in sets]

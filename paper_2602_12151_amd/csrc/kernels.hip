@@ -27,6 +27,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -36,17 +39,14 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-// round-to-nearest-even fp32 -> bf16 bit pattern in the low half (inputs are finite and >= 0 here)
-__device__ __forceinline__ uint32_t bf16_bits_rne(float x) {
-    uint32_t u = __float_as_uint(x);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
-template <int D, int NBUF>
-__global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParams p) {
+template <int D, int NBUF, int WPE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void paged_decode_split_kernel(const SplitParams p) {
     constexpr int KK = D / 32;  // K fragments (16 B) per lane per page = QK MFMAs per page
     constexpr int EV = D / 16;  // V elements per lane per token = PV MFMA tiles per page
     constexpr int VW = EV / 2;  // 32-bit words of V per lane per token
@@ -125,7 +125,9 @@ __global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParam
     float m = -INFINITY;  // running max of (score * scale * log2 e) for head i16
     float l = 0.f;        // this lane's share of the normaliser (its 4 tokens per page)
 
-    auto consume = [&](int slot, int pg) {
+    // One page: scores, online-softmax update, PV accumulate.  `masked` (compile-time) is set only
+    // for a request's ragged last page.
+    auto consume = [&](int slot, int pg, auto masked) {
         // scores: S^T[token 4*g4+r][head i16]
         f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -135,22 +137,29 @@ __global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParam
 #pragma unroll
         for (int r = 0; r < 4; ++r) x[r] = s[r] * p.scale_log2e;
 
-        const int valid = L - pg * PAGE;  // tokens of this page inside the context (uniform)
-        if (valid < PAGE) {
-            // ragged last page: mask by select (the slots may hold anything, NaN included)
+        uint32_t vw[4][VW];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int w = 0; w < VW; ++w) vw[c][w] = vbuf[slot][c][w];
+        if constexpr (decltype(masked)::value) {
+            // mask by select: the slots past the context may hold anything, NaN included
+            const int valid = L - pg * PAGE;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const bool ok = 4 * g4 + r < valid;
                 x[r] = ok ? x[r] : -INFINITY;
 #pragma unroll
-                for (int w = 0; w < VW; ++w) vbuf[slot][r][w] = ok ? vbuf[slot][r][w] : 0u;
+                for (int w = 0; w < VW; ++w) vw[r][w] = ok ? vw[r][w] : 0u;
             }
         }
 
-        float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-        mx = fmaxf(mx, wave_xor_f32(mx, 16));
-        mx = fmaxf(mx, wave_xor_f32(mx, 32));
-        if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {  // some head's max moved: rescale (rare after the first pages)
+        // The running max m is kept equal in the four lanes that share a head.  Lanes exchange
+        // maxima only when some lane's own tokens beat m (rare after the first pages).
+        const float mx_own = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+        if (__builtin_amdgcn_ballot_w64(mx_own > m) != 0) {
+            float mx = fmaxf(mx_own, wave_xor_f32(mx_own, 16));
+            mx = fmaxf(mx, wave_xor_f32(mx, 32));
             const float m_new = fmaxf(m, mx);
             const float alpha = __builtin_amdgcn_exp2f(m - m_new);
             l *= alpha;
@@ -158,34 +167,40 @@ __global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParam
             for (int e = 0; e < EV; ++e) acc[e] *= alpha;
             m = m_new;
         }
-        float pr[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pr[r] = __builtin_amdgcn_exp2f(x[r] - m);
-        l += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+        f32x2 p01, p23;
+        p01[0] = __builtin_amdgcn_exp2f(x[0] - m);
+        p01[1] = __builtin_amdgcn_exp2f(x[1] - m);
+        p23[0] = __builtin_amdgcn_exp2f(x[2] - m);
+        p23[1] = __builtin_amdgcn_exp2f(x[3] - m);
+        l += (p01[0] + p01[1]) + (p23[0] + p23[1]);
 
-        // P^T as the B operand (k = token 4*g4+r, column = head): hi and lo bf16 halves
-        uint32_t hi[4], lo[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            hi[r] = bf16_bits_rne(pr[r]);
-            lo[r] = bf16_bits_rne(pr[r] - __uint_as_float(hi[r] << 16));
-        }
-        const uint2 ph = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-        const uint2 pl = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-        const short4v p_hi = __builtin_bit_cast(short4v, ph);
-        const short4v p_lo = __builtin_bit_cast(short4v, pl);
+        // P^T as the B operand (k = token 4*g4+r, column = head): hi and lo bf16 halves, p = hi + lo + O(2^-17 p)
+        const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(p01, bf16x2));
+        const uint32_t h23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(p23, bf16x2));
+        f32x2 r01, r23;
+        r01[0] = p01[0] - __uint_as_float(h01 << 16);
+        r01[1] = p01[1] - __uint_as_float(h01 & 0xFFFF0000u);
+        r23[0] = p23[0] - __uint_as_float(h23 << 16);
+        r23[1] = p23[1] - __uint_as_float(h23 & 0xFFFF0000u);
+        const uint32_t l01 = __builtin_bit_cast(uint32_t, __builtin_convertvector(r01, bf16x2));
+        const uint32_t l23 = __builtin_bit_cast(uint32_t, __builtin_convertvector(r23, bf16x2));
+        const short4v p_hi = __builtin_bit_cast(short4v, make_uint2(h01, h23));
+        const short4v p_lo = __builtin_bit_cast(short4v, make_uint2(l01, l23));
 
         // V^T as the A operand: row = dim slot i16 (dim EV*i16+e), k = token 4*g4+c
 #pragma unroll
         for (int e = 0; e < EV; ++e) {
             const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-            const uint2 vt = make_uint2(__builtin_amdgcn_perm(vbuf[slot][1][e >> 1], vbuf[slot][0][e >> 1], sel),
-                                        __builtin_amdgcn_perm(vbuf[slot][3][e >> 1], vbuf[slot][2][e >> 1], sel));
+            const uint2 vt = make_uint2(__builtin_amdgcn_perm(vw[1][e >> 1], vw[0][e >> 1], sel),
+                                        __builtin_amdgcn_perm(vw[3][e >> 1], vw[2][e >> 1], sel));
             const short4v a = __builtin_bit_cast(short4v, vt);
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, p_hi, acc[e], 0, 0, 0);
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, p_lo, acc[e], 0, 0, 0);
         }
     };
+    using Full = std::integral_constant<bool, false>;
+    using Ragged = std::integral_constant<bool, true>;
+    const int ragged_page = (L & (PAGE - 1)) ? rec.num_pages - 1 : -1;  // the one page that needs masking, if any
 
     // ---- pipeline: NBUF-1 pages in flight ahead of the one being consumed ----
     // Steady state issues the loads of page pg+NBUF-1 unconditionally before consuming page pg, so
@@ -201,7 +216,10 @@ __global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParam
     auto drain = [&](int slot, int pg) {
 #pragma unroll
         for (int k = 0; k < NBUF - 1; ++k)
-            if (pg + k < pend) consume((slot + k) % NBUF, pg + k);
+            if (pg + k < pend) {
+                if (pg + k == ragged_page) consume((slot + k) % NBUF, pg + k, Ragged{});
+                else consume((slot + k) % NBUF, pg + k, Full{});
+            }
     };
 
     const int main_end = pend - (NBUF - 1);
@@ -214,7 +232,7 @@ __global__ __launch_bounds__(64) void paged_decode_split_kernel(const SplitParam
                 if (pg < main_end) {
                     issue((u + NBUF - 1) % NBUF, next_pid);
                     next_pid = page_id_of(pg + NBUF);
-                    consume(u, pg);
+                    consume(u, pg, Full{});  // the ragged page, if any, is the item's last: never here
                     ++pg;
                 } else {
                     drain(u, pg);
@@ -304,18 +322,46 @@ __global__ __launch_bounds__(64) void paged_decode_merge_kernel(const MergeParam
     for (int d = 0; d < DPL; ++d) dst[d] = num[d] * inv;
 }
 
-constexpr int kNumBuf = 3;
+}  // namespace
+
+namespace {
+
+// Tuning variants (pages in flight per wavefront, wavefronts per SIMD).  The default is the
+// measured best; OSERVE_VARIANT="nbuf,wpe" selects another one for experiments.
+struct Variant { int nbuf, wpe; };
+
+Variant chosen_variant() {
+    Variant d{3, 2};
+    if (const char* e = getenv("OSERVE_VARIANT")) {
+        int a = 0, b = 0;
+        if (sscanf(e, "%d,%d", &a, &b) == 2) d = Variant{a, b};
+    }
+    return d;
+}
+
+template <int D>
+bool launch_split_d(const SplitParams& p, int num_items, hipStream_t stream) {
+    const Variant v = chosen_variant();
+#define OSERVE_TRY(NB, WP)                                                                              \
+    if (v.nbuf == NB && v.wpe == WP) {                                                                  \
+        hipLaunchKernelGGL((paged_decode_split_kernel<D, NB, WP>), dim3(num_items), dim3(64), 0, stream, p); \
+        return true;                                                                                    \
+    }
+    OSERVE_TRY(2, 1) OSERVE_TRY(2, 2) OSERVE_TRY(2, 3) OSERVE_TRY(2, 4)
+    OSERVE_TRY(3, 1) OSERVE_TRY(3, 2) OSERVE_TRY(3, 3)
+    OSERVE_TRY(4, 1) OSERVE_TRY(4, 2) OSERVE_TRY(4, 3)
+#undef OSERVE_TRY
+    return false;
+}
 
 }  // namespace
 
 hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipStream_t stream) {
     if (num_items <= 0) return hipSuccess;
-    if (head_dim == 128)
-        hipLaunchKernelGGL((paged_decode_split_kernel<128, kNumBuf>), dim3(num_items), dim3(64), 0, stream, p);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL((paged_decode_split_kernel<64, kNumBuf>), dim3(num_items), dim3(64), 0, stream, p);
-    else
-        return hipErrorInvalidValue;
+    bool ok = false;
+    if (head_dim == 128) ok = launch_split_d<128>(p, num_items, stream);
+    else if (head_dim == 64) ok = launch_split_d<64>(p, num_items, stream);
+    if (!ok) return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
