@@ -101,9 +101,16 @@ void oserve_plan_destroy(oserve_plan_t* plan); /* null is allowed; the plan's la
 int32_t oserve_plan_batch(const oserve_plan_t* plan);
 int32_t oserve_plan_num_work_items(const oserve_plan_t* plan); /* grid size of the split kernel */
 int32_t oserve_plan_split_pages(const oserve_plan_t* plan);    /* C, in pages */
-/* Splits of request b: count, pages per split, index of its first work item.  Any out pointer may be null. */
+/* Splits of request b: their count, and the size in pages of the largest split of the batch.  Out pointers may be null. */
 oserve_status_t oserve_plan_request(const oserve_plan_t* plan, int32_t b, int32_t* num_splits,
-                                    int32_t* pages_per_split, int32_t* first_item);
+                                    int32_t* max_split_pages);
+/* Inspection of the launch order: the plan holds oserve_plan_num_runs() runs, run i being `num_splits`
+ * consecutive splits of `pages_per_split` pages of one request (the request's very last split may be
+ * shorter), covering its logical pages [page_begin, page_end).  Runs are ordered largest split first;
+ * run i owns work items [first_item, first_item + num_splits * num_kv_heads).
+ * fields = {request, first_item, num_splits, pages_per_split, page_begin, page_end, row_base, total_splits}. */
+int32_t oserve_plan_num_runs(const oserve_plan_t* plan);
+oserve_status_t oserve_plan_run(const oserve_plan_t* plan, int32_t i, int32_t fields[8]);
 /* Bytes of `workspace` the current plan needs, and a bound valid after any update. */
 size_t oserve_plan_workspace_bytes(const oserve_plan_t* plan);
 size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);

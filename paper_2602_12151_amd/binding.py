@@ -12,7 +12,7 @@ import os
 import numpy as np
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liboserve.so")
+_LIB_PATH = os.environ.get("OSERVE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "liboserve.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_CONTEXT_LEN, ERR_WORKSPACE, ERR_PLAN_MISMATCH, ERR_DEVICE = range(7)
 PLAN_RING = 8
@@ -37,11 +37,13 @@ def _load() -> ctypes.CDLL:
     lib.oserve_plan_update.argtypes = [vp, vp, i32]
     lib.oserve_plan_destroy.restype = None
     lib.oserve_plan_destroy.argtypes = [vp]
-    for name in ("oserve_plan_batch", "oserve_plan_num_work_items", "oserve_plan_split_pages"):
+    lib.oserve_plan_run.restype = ctypes.c_int
+    lib.oserve_plan_run.argtypes = [vp, i32, pi32]
+    for name in ("oserve_plan_batch", "oserve_plan_num_work_items", "oserve_plan_split_pages", "oserve_plan_num_runs"):
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = [vp]
     lib.oserve_plan_request.restype = ctypes.c_int
-    lib.oserve_plan_request.argtypes = [vp, i32, pi32, pi32, pi32]
+    lib.oserve_plan_request.argtypes = [vp, i32, pi32, pi32]
     for name in ("oserve_plan_workspace_bytes", "oserve_plan_workspace_bytes_max"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [vp]
@@ -123,12 +125,26 @@ class Plan:
         return lib.oserve_plan_workspace_bytes_max(self._h)
 
     def request(self, b: int):
-        """(num_splits, pages_per_split, first_item) of request b."""
-        s, p, f = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
-        st = lib.oserve_plan_request(self._h, b, ctypes.byref(s), ctypes.byref(p), ctypes.byref(f))
+        """(num_splits of request b, pages of the largest split of the batch)."""
+        s, p = ctypes.c_int32(), ctypes.c_int32()
+        st = lib.oserve_plan_request(self._h, b, ctypes.byref(s), ctypes.byref(p))
         if st != OK:
             raise OserveError(st, "oserve_plan_request")
-        return s.value, p.value, f.value
+        return s.value, p.value
+
+    @property
+    def num_runs(self) -> int:
+        return lib.oserve_plan_num_runs(self._h)
+
+    def run(self, i: int) -> dict:
+        """Run i of the launch order (see oserve_plan_run)."""
+        f = (ctypes.c_int32 * 8)()
+        st = lib.oserve_plan_run(self._h, i, f)
+        if st != OK:
+            raise OserveError(st, "oserve_plan_run")
+        keys = ("request", "first_item", "num_splits", "pages_per_split", "page_begin", "page_end",
+                "row_base", "total_splits")
+        return dict(zip(keys, list(f)))
 
     def enable_timing(self, enable: bool = True) -> None:
         st = lib.oserve_plan_enable_timing(self._h, int(enable))

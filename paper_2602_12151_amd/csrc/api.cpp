@@ -3,6 +3,8 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -10,14 +12,15 @@
 #include "oserve.h"
 #include "plan.h"
 
-using oserve::RequestRecord;
+using oserve::RunRecord;
 using oserve::SplitPlan;
 
 struct oserve_plan {
     SplitPlan host;
     int32_t device_id = -1;
-    // pinned staging for the record upload: OSERVE_PLAN_RING slots of `capacity` records
-    RequestRecord* staging = nullptr;
+    // pinned staging for the upload of run records + request info: OSERVE_PLAN_RING slots
+    char* staging = nullptr;
+    size_t staging_slot_bytes = 0;
     hipEvent_t upload_done[OSERVE_PLAN_RING] = {};
     bool slot_used[OSERVE_PLAN_RING] = {};
     int next_slot = 0;
@@ -88,10 +91,13 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
     pl->host.geo = geo;
     pl->host.capacity = capacity;
     pl->host.split_pages_user = split_tokens / page_size;
-    pl->host.records.reserve(capacity);
-    pl->host.position_of.reserve(capacity);
-    pl->host.scratch_records.reserve(capacity);
-    pl->host.scratch_position.reserve(capacity);
+    pl->host.reserve();
+    pl->staging_slot_bytes = static_cast<size_t>(pl->host.max_runs()) * sizeof(RunRecord) +
+                             static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo);
+    if (const char* e = getenv("OSERVE_PLAN_TUNING")) {  // experiments: "items_per_slot,tail_slots_x16"
+        int a = 0, b = 0;
+        if (sscanf(e, "%d,%d", &a, &b) == 2 && a > 0 && b >= 0) pl->host.tuning = oserve::PlanTuning{a, b};
+    }
     pl->device_id = device_id;
 
     if (device_id >= 0) {
@@ -102,7 +108,7 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
             DeviceGuard guard(device_id);
             ok = guard.ok;
             ok = ok && hipHostMalloc(reinterpret_cast<void**>(&pl->staging),
-                                     sizeof(RequestRecord) * capacity * OSERVE_PLAN_RING,
+                                     pl->staging_slot_bytes * OSERVE_PLAN_RING,
                                      hipHostMallocDefault) == hipSuccess;
             for (int i = 0; ok && i < OSERVE_PLAN_RING; ++i) {
                 ok = hipEventCreateWithFlags(&pl->upload_done[i], hipEventDisableTiming) == hipSuccess;
@@ -144,22 +150,32 @@ int32_t oserve_plan_num_work_items(const oserve_plan_t* plan) { return plan->hos
 int32_t oserve_plan_split_pages(const oserve_plan_t* plan) { return plan->host.split_pages; }
 
 oserve_status_t oserve_plan_request(const oserve_plan_t* plan, int32_t b, int32_t* num_splits,
-                                    int32_t* pages_per_split, int32_t* first_item) {
+                                    int32_t* max_split_pages) {
     if (!plan) return OSERVE_ERR_NULL;
     if (b < 0 || b >= plan->host.batch) return OSERVE_ERR_SHAPE;
-    const RequestRecord& r = plan->host.records[plan->host.position_of[b]];
-    if (num_splits) *num_splits = r.num_splits;
-    if (pages_per_split) *pages_per_split = r.pages_per_split;
-    if (first_item) *first_item = r.first_item;
+    if (num_splits) *num_splits = plan->host.req_info[b].num_splits;
+    if (max_split_pages) *max_split_pages = plan->host.split_pages;
+    return OSERVE_OK;
+}
+
+int32_t oserve_plan_num_runs(const oserve_plan_t* plan) { return static_cast<int32_t>(plan->host.records.size()); }
+
+oserve_status_t oserve_plan_run(const oserve_plan_t* plan, int32_t i, int32_t fields[8]) {
+    if (!plan || !fields) return OSERVE_ERR_NULL;
+    if (i < 0 || i >= static_cast<int32_t>(plan->host.records.size())) return OSERVE_ERR_SHAPE;
+    std::memcpy(fields, &plan->host.records[i], sizeof(RunRecord));
     return OSERVE_OK;
 }
 
 size_t oserve_plan_workspace_bytes(const oserve_plan_t* plan) {
-    return plan->host.layout(plan->host.num_items, plan->host.batch).total;
+    const SplitPlan& hp = plan->host;
+    return hp.layout(hp.num_items, hp.num_row_groups, static_cast<int64_t>(hp.records.size()), hp.batch).total;
 }
 
 size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan) {
-    return plan->host.layout(plan->host.max_items(), plan->host.capacity).total;
+    const SplitPlan& hp = plan->host;
+    const int64_t items = hp.max_items();
+    return hp.layout(items, items / hp.geo.num_kv_heads, hp.max_runs(), hp.capacity).total;
 }
 
 oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, size_t workspace_bytes,
@@ -170,7 +186,8 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
         return OSERVE_ERR_NULL;
     if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
     const SplitPlan& hp = plan->host;
-    const oserve::WorkspaceLayout lay = hp.layout(hp.num_items, hp.batch);
+    const int64_t num_runs = static_cast<int64_t>(hp.records.size());
+    const oserve::WorkspaceLayout lay = hp.layout(hp.num_items, hp.num_row_groups, num_runs, hp.batch);
     if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return OSERVE_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pages) |
@@ -187,18 +204,18 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     if (plan->slot_used[slot] && hipEventSynchronize(plan->upload_done[slot]) != hipSuccess)
         return OSERVE_ERR_DEVICE;
     if (plan->timing && !collect_timing(plan, slot)) return OSERVE_ERR_DEVICE;
-    RequestRecord* stage = plan->staging + static_cast<size_t>(slot) * hp.capacity;
-    std::memcpy(stage, hp.records.data(), sizeof(RequestRecord) * hp.batch);
+    char* stage = plan->staging + static_cast<size_t>(slot) * plan->staging_slot_bytes;
+    std::memcpy(stage + lay.records_off, hp.records.data(), sizeof(RunRecord) * num_runs);
+    std::memcpy(stage + lay.req_info_off, hp.req_info.data(), sizeof(oserve::RequestInfo) * hp.batch);
     char* ws = static_cast<char*>(workspace);
-    if (hipMemcpyAsync(ws + lay.records_off, stage, sizeof(RequestRecord) * hp.batch,
-                       hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (hipMemcpyAsync(ws, stage, lay.upload_bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
         return OSERVE_ERR_DEVICE;
     if (hipEventRecord(plan->upload_done[slot], stream) != hipSuccess) return OSERVE_ERR_DEVICE;
     plan->slot_used[slot] = true;
 
     oserve::SplitParams sp{};
-    sp.records = reinterpret_cast<const RequestRecord*>(ws + lay.records_off);
-    sp.batch = hp.batch;
+    sp.records = reinterpret_cast<const RunRecord*>(ws + lay.records_off);
+    sp.num_runs = static_cast<int32_t>(num_runs);
     sp.q = static_cast<const uint16_t*>(q);
     sp.k_pages = static_cast<const uint16_t*>(k_pages);
     sp.v_pages = static_cast<const uint16_t*>(v_pages);
@@ -222,14 +239,12 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     }
 
     oserve::MergeParams mp{};
-    mp.records = sp.records;
+    mp.req_info = reinterpret_cast<const oserve::RequestInfo*>(ws + lay.req_info_off);
     mp.partial_o = sp.partial_o;
     mp.partial_ml = sp.partial_ml;
     mp.out = out;
     mp.num_q_heads = sp.num_q_heads;
-    mp.num_kv_heads = sp.num_kv_heads;
-    mp.group = sp.group;
-    if (hp.num_items > hp.batch * hp.geo.num_kv_heads) {  // at least one request is split
+    if (hp.num_row_groups > hp.batch) {  // at least one request is split
         if (oserve::launch_merge(mp, hp.geo.head_dim, hp.batch, stream) != hipSuccess)
             return OSERVE_ERR_DEVICE;
     }

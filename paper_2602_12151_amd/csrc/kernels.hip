@@ -58,20 +58,22 @@ void paged_decode_split_kernel(const SplitParams p) {
     const int item = blockIdx.x;
 
     // ---- which (request, kv head, split) is this wavefront's item ----
-    int lo = 0, hi = p.batch;
+    int lo = 0, hi = p.num_runs;
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (p.records[mid].first_item <= item) lo = mid; else hi = mid;
     }
-    const RequestRecord rec = p.records[lo];
+    const RunRecord rec = p.records[lo];
     const int local = item - rec.first_item;
     const int split = local / p.num_kv_heads;
     const int kvh = local - split * p.num_kv_heads;
     const int b = rec.request;
-    const int pbeg = split * rec.pages_per_split;
-    const int pend = min(rec.num_pages, pbeg + rec.pages_per_split);
+    const int pbeg = rec.page_begin + split * rec.pages_per_split;
+    const int pend = min(rec.page_end, pbeg + rec.pages_per_split);
+    // the device copy of the length only decides how much of the page it falls in counts: a value
+    // that disagrees with the plan is clamped into the last page this item owns
     int L = p.context_lens[b];
-    L = min(max(L, (rec.num_pages - 1) * PAGE + 1), rec.num_pages * PAGE);
+    L = min(max(L, (pend - 1) * PAGE + 1), pend * PAGE);
 
     // ---- Q as the B operand of the score MFMA: column = head i16, k-slots = dims ----
     bf16x8 qf[KK];
@@ -200,7 +202,7 @@ void paged_decode_split_kernel(const SplitParams p) {
     };
     using Full = std::integral_constant<bool, false>;
     using Ragged = std::integral_constant<bool, true>;
-    const int ragged_page = (L & (PAGE - 1)) ? rec.num_pages - 1 : -1;  // the one page that needs masking, if any
+    const int ragged_page = (L & (PAGE - 1)) ? pend - 1 : -1;  // the one page that may need masking
 
     // ---- pipeline: NBUF-1 pages in flight ahead of the one being consumed ----
     // Steady state issues the loads of page pg+NBUF-1 unconditionally before consuming page pg, so
@@ -249,11 +251,11 @@ void paged_decode_split_kernel(const SplitParams p) {
         const int h = kvh * p.group + i16;
         float* dst;
         float mul = 1.f;
-        if (rec.num_splits == 1) {
+        if (rec.total_splits == 1) {
             dst = p.out + (static_cast<int64_t>(b) * p.num_q_heads + h) * D;
             mul = 1.f / l_tot;
         } else {
-            const int64_t row = static_cast<int64_t>(item) * p.group + i16;
+            const int64_t row = static_cast<int64_t>(rec.row_base + split) * p.num_q_heads + h;
             dst = p.partial_o + row * D;
             if (g4 == 0) {
                 p.partial_ml[row * 2] = m;
@@ -283,16 +285,14 @@ template <int D>
 __global__ __launch_bounds__(64) void paged_decode_merge_kernel(const MergeParams p) {
     constexpr int DPL = D / 64;  // dims per lane
     const int lane = threadIdx.x;
-    const int pos = blockIdx.x / p.num_q_heads;
-    const int h = blockIdx.x - pos * p.num_q_heads;
-    const RequestRecord rec = p.records[pos];
-    const int S = rec.num_splits;
+    const int b = blockIdx.x / p.num_q_heads;
+    const int h = blockIdx.x - b * p.num_q_heads;
+    const RequestInfo info = p.req_info[b];
+    const int S = info.num_splits;
     if (S == 1) return;  // the split kernel already wrote `out`
-    const int kvh = h / p.group;
-    const int gi = h - kvh * p.group;
-    // row of split s: (first_item + s*Hkv + kvh) * group + gi
-    const int64_t row0 = (static_cast<int64_t>(rec.first_item) + kvh) * p.group + gi;
-    const int64_t row_step = static_cast<int64_t>(p.num_kv_heads) * p.group;
+    // row of split s: (split_base + s) * Hq + h
+    const int64_t row0 = static_cast<int64_t>(info.split_base) * p.num_q_heads + h;
+    const int64_t row_step = p.num_q_heads;
 
     float mmax = -INFINITY;
     for (int s = lane; s < S; s += 64) mmax = fmaxf(mmax, p.partial_ml[(row0 + s * row_step) * 2]);
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(64) void paged_decode_merge_kernel(const MergeParam
             num[0] += w * o[0];
         }
     }
-    float* dst = p.out + (static_cast<int64_t>(rec.request) * p.num_q_heads + h) * D + lane * DPL;
+    float* dst = p.out + (static_cast<int64_t>(b) * p.num_q_heads + h) * D + lane * DPL;
     const float inv = 1.f / den;
 #pragma unroll
     for (int d = 0; d < DPL; ++d) dst[d] = num[d] * inv;
@@ -331,7 +331,7 @@ namespace {
 struct Variant { int nbuf, wpe; };
 
 Variant chosen_variant() {
-    Variant d{3, 2};
+    Variant d{3, 1};
     if (const char* e = getenv("OSERVE_VARIANT")) {
         int a = 0, b = 0;
         if (sscanf(e, "%d,%d", &a, &b) == 2) d = Variant{a, b};

@@ -1,4 +1,4 @@
-// Internal: host-side split plan shared by plan.cpp (sizing) and api.hip (launch).
+// Internal: host-side split plan shared by plan.cpp (sizing) and api.cpp (launch).
 #pragma once
 #include <cstddef>
 #include <cstdint>
@@ -8,18 +8,25 @@
 
 namespace oserve {
 
-// One record per request, in launch order (longest split first).  Uploaded to
-// the front of the workspace; the kernels find their request by binary search
-// over first_item.
-struct RequestRecord {
+// A run = consecutive splits of one request that all have the same size (the very last split of a
+// request may be shorter).  One record per run, in launch order (largest splits first).  Uploaded
+// to the front of the workspace; a wavefront finds its run by binary search over first_item.
+struct RunRecord {
     int32_t request;          // index b into q / block_table / context_lens / out
-    int32_t first_item;       // index of this request's first work item
-    int32_t num_splits;       // S_b
-    int32_t pages_per_split;  // ceil(N_b / S_b)
-    int32_t num_pages;        // N_b = ceil(L_b / page_size)
-    int32_t pad[3];
+    int32_t first_item;       // index of the run's first work item; items are (split, kv head), kv head fastest
+    int32_t num_splits;       // splits in this run
+    int32_t pages_per_split;  // size of each of them
+    int32_t page_begin;       // logical pages [page_begin, page_end) of the request belong to the run
+    int32_t page_end;
+    int32_t row_base;         // partial-result row group of the run's first split
+    int32_t total_splits;     // splits of the whole request (1: the item writes `out` itself)
 };
-static_assert(sizeof(RequestRecord) == 32, "record layout is part of the kernel interface");
+static_assert(sizeof(RunRecord) == 32, "record layout is part of the kernel interface");
+
+struct RequestInfo {          // per request, in request order; read by the merge kernel
+    int32_t split_base;       // first partial-result row group of the request
+    int32_t num_splits;
+};
 
 struct Geometry {
     int32_t num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq;
@@ -27,7 +34,23 @@ struct Geometry {
 };
 
 struct WorkspaceLayout {
-    size_t records_off, partial_o_off, partial_ml_off, total;
+    size_t records_off, req_info_off, partial_o_off, partial_ml_off, total;
+    size_t upload_bytes;      // records + request info are contiguous and uploaded together
+};
+
+// Split sizing constants.  In automatic mode the largest split C is a multiple of kSplitGranule
+// chosen so that the batch yields about kItemsPerSlot full-size items per wavefront slot
+// (kSlotsPerCu per compute unit); the end of every long request is cut into smaller splits taken
+// from the ladder C, C/2, C/4, ... >= kSplitGranule (each rounded up to the granule), so a request
+// contributes at most kMaxRunsPerRequest runs.
+constexpr int32_t kSplitGranule = 12;
+constexpr int32_t kMaxAutoSplitPages = 384;
+constexpr int32_t kMaxRunsPerRequest = 8;
+constexpr int32_t kSlotsPerCu = 4;
+
+struct PlanTuning {
+    int32_t items_per_slot = 3;   // full-size items per wavefront slot
+    int32_t tail_slots_x16 = 8;   // tapered share = this/16 * slots * C page-units (see build())
 };
 
 // Pure host logic (no HIP): everything the CPU tests exercise.
@@ -36,25 +59,24 @@ struct SplitPlan {
     int32_t capacity = 0;
     int32_t split_pages_user = 0;   // 0 = automatic
     int32_t num_cus = 256;
+    PlanTuning tuning{};
     int32_t batch = 0;
     int32_t split_pages = 0;        // C actually used
+    int32_t tail_q8 = 0;            // share of each long request that is tapered, in 1/256 (0: none)
     int32_t num_items = 0;
-    std::vector<RequestRecord> records;     // launch order, size batch
-    std::vector<int32_t> position_of;       // request -> index into records
-    std::vector<RequestRecord> scratch_records;   // build() works here, then swaps
-    std::vector<int32_t> scratch_position;
+    int32_t num_row_groups = 0;     // sum of splits over all requests
+    std::vector<RunRecord> records;         // launch order
+    std::vector<RequestInfo> req_info;      // request order
+    std::vector<RunRecord> scratch_records; // build() works here, then swaps
+    std::vector<RequestInfo> scratch_info;
 
     static oserve_status_t check_geometry(const Geometry& g, int32_t batch, int32_t capacity,
                                           int32_t split_tokens);
+    void reserve();
     oserve_status_t build(const int32_t* lens, int32_t n);
-    WorkspaceLayout layout(int64_t items, int32_t n) const;
+    WorkspaceLayout layout(int64_t items, int64_t row_groups, int64_t runs, int32_t n) const;
     int64_t max_items() const;
+    int64_t max_runs() const { return static_cast<int64_t>(capacity) * kMaxRunsPerRequest; }
 };
-
-// Target number of work items: waves the device keeps resident times an
-// oversubscription factor, so the tail of the launch is short.
-constexpr int32_t kWavesPerCu = 8;
-constexpr int32_t kOversubscribe = 4;
-constexpr int32_t kMinSplitPages = 8;
 
 }  // namespace oserve

@@ -1,0 +1,142 @@
+"""Host-side split planning through the C ABI (no GPU): every page of every request is covered by
+exactly one split, the launch order is longest-first, sizes and bounds are consistent."""
+import numpy as np
+import pytest
+
+from paper_2602_12151_amd import binding, workloads as wl
+
+
+def make_plan(lens, hq=32, hkv=8, d=128, split_tokens=0, capacity=None):
+    lens = np.asarray(lens, dtype=np.int32)
+    width = int(wl.pages_needed(lens).max())
+    return binding.Plan(lens, hq, hkv, d, 16, width, split_tokens, -1, capacity)
+
+
+def check_plan(plan, lens, hkv):
+    need = wl.pages_needed(np.asarray(lens))
+    runs = [plan.run(i) for i in range(plan.num_runs)]
+    covered = [np.zeros(n, dtype=np.int32) for n in need]
+    items = 0
+    prev_size = None
+    rows_seen = set()
+    for r in runs:
+        b = r["request"]
+        assert r["first_item"] == items
+        items += r["num_splits"] * hkv
+        assert r["num_splits"] >= 1 and r["pages_per_split"] >= 1
+        assert 0 <= r["page_begin"] < r["page_end"] <= need[b]
+        # all splits of a run are non-empty and only the last one may be short
+        span = r["page_end"] - r["page_begin"]
+        assert (r["num_splits"] - 1) * r["pages_per_split"] < span <= r["num_splits"] * r["pages_per_split"]
+        covered[b][r["page_begin"]:r["page_end"]] += 1
+        if prev_size is not None:
+            assert r["pages_per_split"] <= prev_size          # longest first
+        prev_size = r["pages_per_split"]
+        assert r["pages_per_split"] <= plan.split_pages
+        assert r["total_splits"] == plan.request(b)[0]
+        for s in range(r["num_splits"]):
+            row = r["row_base"] + s
+            assert row not in rows_seen
+            rows_seen.add(row)
+    assert items == plan.num_work_items
+    for c in covered:
+        assert (c == 1).all()
+    total_splits = sum(plan.request(b)[0] for b in range(len(lens)))
+    assert rows_seen == set(range(total_splits))
+    assert plan.workspace_bytes <= plan.workspace_bytes_max
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_automatic_plan_covers_every_page_once(idx):
+    w = wl.WORKLOADS[idx]
+    lens = wl.context_lens(w)
+    plan = make_plan(lens, w.num_q_heads, w.num_kv_heads, w.head_dim)
+    check_plan(plan, lens, w.num_kv_heads)
+    assert plan.split_pages % 12 == 0
+
+
+@pytest.mark.parametrize("split_tokens", [16, 48, 64, 256, 1024, 4096])
+def test_explicit_split_size(split_tokens):
+    lens = [1, 15, 16, 17, 255, 256, 257, 1000, 4097, 33000]
+    plan = make_plan(lens, split_tokens=split_tokens)
+    check_plan(plan, lens, 8)
+    assert plan.split_pages == split_tokens // 16
+    for b, L in enumerate(lens):
+        pages = (L + 15) // 16
+        s0 = -(-pages // plan.split_pages)
+        pps = -(-pages // s0)
+        assert plan.request(b)[0] == -(-pages // pps)      # near-equal splits
+
+
+def test_tapered_tail_of_a_long_request():
+    """In automatic mode a long request ends in splits that shrink down to the granule."""
+    w = wl.WORKLOADS[3]
+    lens = wl.context_lens(w)
+    plan = make_plan(lens, w.num_q_heads, w.num_kv_heads, w.head_dim)
+    b = int(np.argmax(lens))
+    mine = sorted((plan.run(i) for i in range(plan.num_runs) if plan.run(i)["request"] == b),
+                  key=lambda r: r["page_begin"])
+    sizes = [r["pages_per_split"] for r in mine]
+    assert sizes[0] == plan.split_pages and sizes[-1] == 12
+    assert all(a >= b_ for a, b_ in zip(sizes, sizes[1:]))
+    assert len(set(sizes)) >= 4
+
+
+def test_update_reuses_the_plan_and_errors():
+    plan = make_plan([100, 5000, 20], capacity=8)
+    lens2 = [7, 9000, 300, 1, 64]
+    # widths: the plan was created for max_pages_per_seq = ceil(5000/16); 9000 tokens do not fit
+    with pytest.raises(binding.OserveError) as e:
+        plan.update(np.asarray(lens2, dtype=np.int32))
+    assert e.value.status == binding.ERR_CONTEXT_LEN
+    plan.update(np.asarray([7, 4000, 300, 1, 64], dtype=np.int32))
+    check_plan(plan, [7, 4000, 300, 1, 64], 8)
+    with pytest.raises(binding.OserveError) as e:
+        plan.update(np.ones(9, dtype=np.int32))
+    assert e.value.status == binding.ERR_PLAN_MISMATCH
+    with pytest.raises(binding.OserveError) as e:
+        plan.update(np.asarray([0, 5], dtype=np.int32))
+    assert e.value.status == binding.ERR_CONTEXT_LEN
+
+
+def test_create_rejects_bad_shapes():
+    lens = np.asarray([100], dtype=np.int32)
+    bad = [
+        dict(num_q_heads=30, num_kv_heads=8),       # not a multiple
+        dict(num_q_heads=64, num_kv_heads=2),       # group 32 > 16
+        dict(head_dim=96),
+        dict(page_size=32),
+        dict(split_tokens=40),                      # not a multiple of the page size
+    ]
+    for kw in bad:
+        args = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=16, max_pages_per_seq=16,
+                    split_tokens=0, device_id=-1)
+        args.update(kw)
+        with pytest.raises(binding.OserveError) as e:
+            binding.Plan(lens, **args)
+        assert e.value.status == binding.ERR_SHAPE
+    with pytest.raises(binding.OserveError) as e:
+        binding.Plan(np.asarray([300], dtype=np.int32), 32, 8, 128, 16, 16, 0, -1)   # 300 tokens > 16 pages
+    assert e.value.status == binding.ERR_CONTEXT_LEN
+
+
+def test_plan_without_device_cannot_launch():
+    import ctypes
+    plan = make_plan([100, 200])
+    st = binding.lib.oserve_paged_decode_attn(plan.handle, ctypes.c_void_p(256), 1 << 20, ctypes.c_void_p(256),
+                                             ctypes.c_void_p(256), ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                             ctypes.c_void_p(256), ctypes.c_float(1.0), ctypes.c_void_p(256), None)
+    assert st == binding.ERR_PLAN_MISMATCH
+    st = binding.lib.oserve_paged_decode_attn(plan.handle, None, 0, None, None, None, None, None,
+                                             ctypes.c_float(1.0), None, None)
+    assert st == binding.ERR_NULL
+
+
+def test_library_exports_every_declared_symbol():
+    import re, os
+    hdr = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "oserve.h")).read()
+    names = set(re.findall(r"\b(oserve_[a-z_]+)\s*\(", hdr))
+    assert {"oserve_plan_create", "oserve_paged_decode_attn", "oserve_plan_update"} <= names
+    for n in names:
+        assert hasattr(binding.lib, n), n
+    assert binding.status_string(0) == "ok"
