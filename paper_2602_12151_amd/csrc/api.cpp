@@ -20,6 +20,7 @@ struct oserve_plan {
     int32_t device_id = -1;
     // pinned staging for the upload of run records + request info: OSERVE_PLAN_RING slots
     char* staging = nullptr;
+    char* staging_dev = nullptr;   // the same memory as the device addresses it
     size_t staging_slot_bytes = 0;
     hipEvent_t upload_done[OSERVE_PLAN_RING] = {};
     bool slot_used[OSERVE_PLAN_RING] = {};
@@ -92,8 +93,8 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
     pl->host.capacity = capacity;
     pl->host.split_pages_user = split_tokens / page_size;
     pl->host.reserve();
-    pl->staging_slot_bytes = static_cast<size_t>(pl->host.max_runs()) * sizeof(RunRecord) +
-                             static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo);
+    pl->staging_slot_bytes = (static_cast<size_t>(pl->host.max_runs()) * sizeof(RunRecord) +
+                              static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo) + 255) & ~static_cast<size_t>(255);
     if (const char* e = getenv("OSERVE_PLAN_TUNING")) {  // experiments: "items_per_slot,tail_slots_x16"
         int a = 0, b = 0;
         if (sscanf(e, "%d,%d", &a, &b) == 2 && a > 0 && b >= 0) pl->host.tuning = oserve::PlanTuning{a, b};
@@ -110,6 +111,7 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
             ok = ok && hipHostMalloc(reinterpret_cast<void**>(&pl->staging),
                                      pl->staging_slot_bytes * OSERVE_PLAN_RING,
                                      hipHostMallocDefault) == hipSuccess;
+            ok = ok && hipHostGetDevicePointer(reinterpret_cast<void**>(&pl->staging_dev), pl->staging, 0) == hipSuccess;
             for (int i = 0; ok && i < OSERVE_PLAN_RING; ++i) {
                 ok = hipEventCreateWithFlags(&pl->upload_done[i], hipEventDisableTiming) == hipSuccess;
                 ok = ok && hipEventCreate(&pl->t_begin[i]) == hipSuccess;
@@ -208,7 +210,8 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     std::memcpy(stage + lay.records_off, hp.records.data(), sizeof(RunRecord) * num_runs);
     std::memcpy(stage + lay.req_info_off, hp.req_info.data(), sizeof(oserve::RequestInfo) * hp.batch);
     char* ws = static_cast<char*>(workspace);
-    if (hipMemcpyAsync(ws, stage, lay.upload_bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (oserve::launch_upload(plan->staging_dev + static_cast<size_t>(slot) * plan->staging_slot_bytes, ws,
+                              lay.upload_bytes, stream) != hipSuccess)
         return OSERVE_ERR_DEVICE;
     if (hipEventRecord(plan->upload_done[slot], stream) != hipSuccess) return OSERVE_ERR_DEVICE;
     plan->slot_used[slot] = true;

@@ -31,6 +31,8 @@ struct MergeParams {
     int32_t num_q_heads;
 };
 
+// src_host: pinned host memory as the device addresses it; copies `bytes` (rounded up to 16)
+hipError_t launch_upload(const void* src_host, void* dst, size_t bytes, hipStream_t stream);
 hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipStream_t stream);
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 

@@ -44,6 +44,15 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
+// Copies the plan's run records and request info from pinned host memory into the workspace.  One
+// workgroup; a kernel rather than a memcpy so that the split kernel follows it in the same queue
+// without a copy-engine hand-over.
+constexpr int kUploadThreads = 1024;
+__global__ __launch_bounds__(kUploadThreads) void upload_plan_kernel(const uint4* __restrict__ src_host,
+                                                                     uint4* __restrict__ dst, int n16) {
+    for (int i = threadIdx.x; i < n16; i += kUploadThreads) dst[i] = src_host[i];
+}
+
 template <int D, int NBUF, int WPE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void paged_decode_split_kernel(const SplitParams p) {
@@ -303,6 +312,7 @@ __global__ __launch_bounds__(64) void paged_decode_merge_kernel(const MergeParam
 #pragma unroll
     for (int d = 0; d < DPL; ++d) num[d] = 0.f;
     float den = 0.f;
+#pragma unroll 4
     for (int s = 0; s < S; ++s) {
         const int64_t row = row0 + s * row_step;
         const float w = __builtin_amdgcn_exp2f(p.partial_ml[row * 2] - mmax);
@@ -362,6 +372,13 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
     if (head_dim == 128) ok = launch_split_d<128>(p, num_items, stream);
     else if (head_dim == 64) ok = launch_split_d<64>(p, num_items, stream);
     if (!ok) return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_upload(const void* src_host, void* dst, size_t bytes, hipStream_t stream) {
+    hipLaunchKernelGGL(upload_plan_kernel, dim3(1), dim3(kUploadThreads), 0, stream,
+                       static_cast<const uint4*>(src_host), static_cast<uint4*>(dst),
+                       static_cast<int>((bytes + 15) / 16));
     return hipGetLastError();
 }
 

@@ -42,7 +42,7 @@ WorkspaceLayout SplitPlan::layout(int64_t items, int64_t row_groups, int64_t run
     w.records_off = 0;
     w.req_info_off = static_cast<size_t>(runs) * sizeof(RunRecord);
     w.upload_bytes = w.req_info_off + static_cast<size_t>(n) * sizeof(RequestInfo);
-    w.partial_o_off = align(w.upload_bytes);
+    w.partial_o_off = align(w.upload_bytes + 16);  // the upload kernel copies whole 16-byte words
     const size_t rows = static_cast<size_t>(row_groups) * geo.num_q_heads;
     w.partial_ml_off = w.partial_o_off + align(rows * geo.head_dim * sizeof(float));
     w.total = w.partial_ml_off + align(rows * 2 * sizeof(float));
