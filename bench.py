@@ -24,6 +24,11 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
+# HBM bytes per launch of the split kernel (read + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# scaled by a plain copy of known size: profiles/split_kernel_cfg3_heterogeneous_mix.md.  Only the
+# workload that was profiled has an entry; the others report null.
+MEASURED_TRAFFIC_BYTES = {3: 6_955_500_000 + 14_200_000}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -158,7 +163,8 @@ def main():
                    "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms / args.steps, 5)},
         "roofline": {"bound": "hbm", "kernel": "paged_decode_split_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": None, "avg_kernel_ms": round(split_ms, 5), "launches_timed": cnt,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.index) if args.split_tokens == 0 else None,
+                     "avg_kernel_ms": round(split_ms, 5), "launches_timed": cnt,
                      "algorithmic_bytes_per_launch": nbytes},
     }
     if not args.no_cpu_baseline:

@@ -19,17 +19,19 @@
  *     k_t = k_pages[block_table[b][t / page_size]][j][t % page_size][:]   t = 0..L-1
  *     out[b][h][:] = sum_t softmax_t(scale * <q[b][h], k_t>) * v_t
  *
- * computed in two kernels on the caller's stream: a split kernel (one
- * wavefront per (request, kv head, sequence split), online softmax, fp32
- * accumulation, bf16 MFMA) and a log-sum-exp merge of the splits.
+ * computed on the caller's stream by a split kernel (one wavefront per
+ * (request, kv head, sequence split), online softmax, fp32 accumulation, bf16
+ * MFMA) and a log-sum-exp merge of the splits; a third, tiny kernel first
+ * copies the plan's records into the workspace.
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name ends in _host; `plan`
  *     objects are host objects owned by the library.
  *   - The caller owns all device memory, including `workspace`.  Launch calls
  *     never allocate or free device memory and never synchronise with the
- *     device, except that a plan used for more than OSERVE_PLAN_RING launches
- *     without the stream draining blocks on the oldest launch's upload.
+ *     device, with one exception: a plan keeps OSERVE_PLAN_RING pinned staging
+ *     slots for its records, so the (OSERVE_PLAN_RING+1)-th launch of a plan
+ *     waits until the oldest launch's record copy has run on the device.
  *   - Every function returns a status code; nothing throws or aborts.
  *   - hipStream_t is passed as void* (null = the default stream).
  */
@@ -63,12 +65,16 @@ typedef enum {
 
 /*
  * Plan: sizes the sequence splits of one batch from its context lengths (the
- * step that lets short and long requests fill the GPU together).  The
- * sequence of request b (N_b pages) is cut into S_b = ceil(N_b / C) splits of
- * ceil(N_b / S_b) pages each, where C (pages) is `split_tokens / page_size`,
- * or, when `split_tokens` is 0, is chosen so that the batch yields a few work
- * items per resident wavefront of the device.  Work items (request, kv head,
- * split) are ordered longest split first.  Host-only, O(batch log batch).
+ * step that lets short and long requests fill the GPU together).  With an
+ * explicit `split_tokens` the sequence of request b (N_b pages) is cut into
+ * S_b = ceil(N_b / C) splits of ceil(N_b / S_b) pages, C = split_tokens /
+ * page_size.  With `split_tokens` = 0 the planner picks C (a multiple of 12
+ * pages) so that the batch yields a few full-size work items per resident
+ * wavefront of the device, requests of at most C pages stay whole, and longer
+ * ones are cut into full-size splits followed by a tail of splits that shrink
+ * (C, C/2, C/4, ... 12 pages) in proportion to what is left of the request.
+ * Work items (request, kv head, split) are launched largest split first, so
+ * the small ones fill the end of the launch.  Host-only, O(batch log batch).
  *
  *   context_lens_host  [batch] int32, host memory, each in [1, max_pages_per_seq*page_size]
  *   max_pages_per_seq  row stride (entries) of the block table passed at launch
@@ -117,22 +123,26 @@ size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);
 
 /*
  * One decode step of paged attention (definition at the top of this file).
- * Enqueues on `stream`: a small upload of the plan's per-request records into
- * `workspace`, the split kernel, and the merge kernel.  Returns without
- * waiting.
+ * Enqueues on `stream`: a one-workgroup kernel that copies the plan's records
+ * from pinned host memory into `workspace`, the split kernel, and (if any
+ * request is split) the merge kernel.  Returns without waiting.  The records
+ * are staged at call time, so the plan may be updated as soon as the call
+ * returns; it must not be destroyed before the launch has run.
  *
  *   workspace      device, >= oserve_plan_workspace_bytes(plan), 256-byte aligned;
  *                  contents are scratch.  Two launches that overlap in time must
  *                  not share a workspace.
  *   q              bf16 [batch, num_q_heads, head_dim], contiguous
  *   k_pages        bf16 [num_pages, num_kv_heads, page_size, head_dim], contiguous,
- *   v_pages        same shape; 16-byte aligned.  Slots at or beyond a request's
- *                  context length, and pages no table row names, are never read.
+ *   v_pages        same shape; 16-byte aligned.  Slots at or beyond a request's context
+ *                  length (in its last page) may be read but never influence the result,
+ *                  whatever they hold; pages no table row names are never read.
  *   block_table    int32 [batch, max_pages_per_seq]: physical page of logical page p of
  *                  request b.  Only the first ceil(L_b / page_size) entries of a row are read.
  *   context_lens   int32 [batch], the device copy of the lengths the plan was built from.
- *                  A device value that disagrees with the plan is clamped into the last
- *                  planned page of the request (no out-of-range read results).
+ *                  The kernels take the split boundaries from the plan and from this array
+ *                  only how many tokens of a request's last page count; a value that
+ *                  disagrees with the plan is clamped into that page (no out-of-range read).
  *   scale          multiplies the fp32 score q.k (not q)
  *   out            fp32 [batch, num_q_heads, head_dim], contiguous
  *
