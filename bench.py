@@ -147,6 +147,24 @@ def main():
         op.plan.enable_timing(False)
     split_ms = tot / max(cnt, 1)
 
+    # distribution of single steps (events between the steps; not what `value` is computed from)
+    n_single = min(args.steps, 50)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_single + 1)]
+    evs[0].record()
+    for i in range(n_single):
+        step(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    singles = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_single))
+    # the host re-plan alone
+    lens_host = sets[0].context_lens_host
+    n_plan = 200
+    t0 = time.perf_counter()
+    for _ in range(n_plan):
+        plan0.update(lens_host)
+    plan_us = (time.perf_counter() - t0) / n_plan * 1e6
+    prop = torch.cuda.get_device_properties(0)
+
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     achieved = nbytes / (split_ms * 1e-3) / 1e9
     result = {
@@ -160,7 +178,12 @@ def main():
                                f"head_dim {w.head_dim}, page 16, {int(sets[0].context_lens_host.sum())} tokens, "
                                f"{nbytes / 1e9:.3f} GB K+V per step",
                    "work_items": plan0.num_work_items, "split_pages": plan0.split_pages,
-                   "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms / args.steps, 5)},
+                   "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms / args.steps, 5),
+                   "single_step_us_median": round(singles[len(singles) // 2] * 1e3, 2),
+                   "single_step_us_min": round(singles[0] * 1e3, 2),
+                   "host_plan_update_us": round(plan_us, 2),
+                   "device": f"{prop.name}, {prop.multi_processor_count} CUs, "
+                             f"{prop.total_memory / 2**30:.0f} GiB"},
         "roofline": {"bound": "hbm", "kernel": "paged_decode_split_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.index) if args.split_tokens == 0 else None,

@@ -357,9 +357,8 @@ bool launch_split_d(const SplitParams& p, int num_items, hipStream_t stream) {
         hipLaunchKernelGGL((paged_decode_split_kernel<D, NB, WP>), dim3(num_items), dim3(64), 0, stream, p); \
         return true;                                                                                    \
     }
-    OSERVE_TRY(2, 1) OSERVE_TRY(2, 2) OSERVE_TRY(2, 3) OSERVE_TRY(2, 4)
-    OSERVE_TRY(3, 1) OSERVE_TRY(3, 2) OSERVE_TRY(3, 3)
-    OSERVE_TRY(4, 1) OSERVE_TRY(4, 2) OSERVE_TRY(4, 3)
+    // more wavefronts per SIMD than these would spill the register ring to scratch memory
+    OSERVE_TRY(2, 1) OSERVE_TRY(2, 2) OSERVE_TRY(3, 1) OSERVE_TRY(3, 2) OSERVE_TRY(4, 1)
 #undef OSERVE_TRY
     return false;
 }
