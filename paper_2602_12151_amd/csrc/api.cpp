@@ -94,10 +94,11 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
     pl->host.split_pages_user = split_tokens / page_size;
     pl->host.reserve();
     pl->staging_slot_bytes = (static_cast<size_t>(pl->host.max_runs()) * sizeof(RunRecord) +
-                              static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo) + 255) & ~static_cast<size_t>(255);
-    if (const char* e = getenv("OSERVE_PLAN_TUNING")) {  // experiments: "items_per_slot,tail_slots_x16"
-        int a = 0, b = 0;
-        if (sscanf(e, "%d,%d", &a, &b) == 2 && a > 0 && b >= 0) pl->host.tuning = oserve::PlanTuning{a, b};
+                              static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo) + 16 + 255) & ~static_cast<size_t>(255);
+    if (const char* e = getenv("OSERVE_PLAN_TUNING")) {  // experiments: "items_per_slot_x4,tail_slots_x16,max_split_pages"
+        int a = 0, b = 0, c = 0;
+        if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && a > 0 && b >= 0 && c >= 12 && c <= 4096)
+            pl->host.tuning = oserve::PlanTuning{a, b, c};
     }
     pl->device_id = device_id;
 
@@ -206,19 +207,26 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     if (plan->slot_used[slot] && hipEventSynchronize(plan->upload_done[slot]) != hipSuccess)
         return OSERVE_ERR_DEVICE;
     if (plan->timing && !collect_timing(plan, slot)) return OSERVE_ERR_DEVICE;
-    char* stage = plan->staging + static_cast<size_t>(slot) * plan->staging_slot_bytes;
-    std::memcpy(stage + lay.records_off, hp.records.data(), sizeof(RunRecord) * num_runs);
-    std::memcpy(stage + lay.req_info_off, hp.req_info.data(), sizeof(oserve::RequestInfo) * hp.batch);
+    // slot layout: [run records][request info]; both 16-byte aligned
+    const size_t slot_off = static_cast<size_t>(slot) * plan->staging_slot_bytes;
+    const size_t info_off = sizeof(RunRecord) * static_cast<size_t>(num_runs);
+    std::memcpy(plan->staging + slot_off, hp.records.data(), info_off);
+    std::memcpy(plan->staging + slot_off + info_off, hp.req_info.data(), sizeof(oserve::RequestInfo) * hp.batch);
     char* ws = static_cast<char*>(workspace);
-    if (oserve::launch_upload(plan->staging_dev + static_cast<size_t>(slot) * plan->staging_slot_bytes, ws,
-                              lay.upload_bytes, stream) != hipSuccess)
-        return OSERVE_ERR_DEVICE;
-    if (hipEventRecord(plan->upload_done[slot], stream) != hipSuccess) return OSERVE_ERR_DEVICE;
+    oserve::ExpandParams ep{};
+    ep.records_host = reinterpret_cast<const RunRecord*>(plan->staging_dev + slot_off);
+    ep.num_runs = static_cast<int32_t>(num_runs);
+    ep.req_info_host = reinterpret_cast<const oserve::RequestInfo*>(plan->staging_dev + slot_off + info_off);
+    ep.req_info = reinterpret_cast<oserve::RequestInfo*>(ws + lay.req_info_off);
+    ep.batch = hp.batch;
+    ep.items = reinterpret_cast<oserve::ItemDesc*>(ws + lay.items_off);
+    ep.num_kv_heads = hp.geo.num_kv_heads;
+    ep.kv_heads_magic = static_cast<uint32_t>((1ull << 32) / static_cast<uint32_t>(hp.geo.num_kv_heads)) + 1u;
+    if (oserve::launch_expand(ep, stream, plan->upload_done[slot]) != hipSuccess) return OSERVE_ERR_DEVICE;
     plan->slot_used[slot] = true;
 
     oserve::SplitParams sp{};
-    sp.records = reinterpret_cast<const RunRecord*>(ws + lay.records_off);
-    sp.num_runs = static_cast<int32_t>(num_runs);
+    sp.items = ep.items;
     sp.q = static_cast<const uint16_t*>(q);
     sp.k_pages = static_cast<const uint16_t*>(k_pages);
     sp.v_pages = static_cast<const uint16_t*>(v_pages);
@@ -233,13 +241,11 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     sp.group = hp.geo.group();
     sp.max_pages_per_seq = hp.geo.max_pages_per_seq;
 
-    if (plan->timing && hipEventRecord(plan->t_begin[slot], stream) != hipSuccess) return OSERVE_ERR_DEVICE;
-    if (oserve::launch_split(sp, hp.geo.head_dim, hp.num_items, stream) != hipSuccess)
+    if (oserve::launch_split(sp, hp.geo.head_dim, hp.num_items, stream,
+                             plan->timing ? plan->t_begin[slot] : nullptr,
+                             plan->timing ? plan->t_end[slot] : nullptr) != hipSuccess)
         return OSERVE_ERR_DEVICE;
-    if (plan->timing) {
-        if (hipEventRecord(plan->t_end[slot], stream) != hipSuccess) return OSERVE_ERR_DEVICE;
-        plan->t_pending[slot] = true;
-    }
+    if (plan->timing) plan->t_pending[slot] = true;
 
     oserve::MergeParams mp{};
     mp.req_info = reinterpret_cast<const oserve::RequestInfo*>(ws + lay.req_info_off);

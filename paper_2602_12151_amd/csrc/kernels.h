@@ -9,8 +9,7 @@
 namespace oserve {
 
 struct SplitParams {
-    const RunRecord* records;      // device copy, launch order
-    int32_t num_runs;
+    const ItemDesc* items;         // one per work item, launch order
     const uint16_t* q;             // bf16 bits [B, Hq, D]
     const uint16_t* k_pages;       // bf16 bits [P, Hkv, 16, D]
     const uint16_t* v_pages;
@@ -31,9 +30,24 @@ struct MergeParams {
     int32_t num_q_heads;
 };
 
-// src_host: pinned host memory as the device addresses it; copies `bytes` (rounded up to 16)
-hipError_t launch_upload(const void* src_host, void* dst, size_t bytes, hipStream_t stream);
-hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipStream_t stream);
+struct ExpandParams {
+    const RunRecord* records_host;    // pinned host memory as the device addresses it, 16-byte aligned
+    int32_t num_runs;
+    const RequestInfo* req_info_host; // pinned host memory, 16-byte aligned, readable up to a 16-byte boundary
+    RequestInfo* req_info;            // workspace copy (whole 16-byte words are written)
+    int32_t batch;
+    ItemDesc* items;                  // workspace, one descriptor per work item
+    int32_t num_kv_heads;
+    uint32_t kv_heads_magic;          // floor(2^32 / num_kv_heads) + 1: (k * magic) >> 32 == k / num_kv_heads for k < 2^20
+                                      // (unused when num_kv_heads == 1, where it does not fit 32 bits)
+};
+
+// The events are attached to the kernel's own dispatch (no marker packets between the kernels):
+// `done` completes when the expand kernel has finished; `start`/`stop`, if non-null, take the split
+// kernel's begin and end timestamps.
+hipError_t launch_expand(const ExpandParams& p, hipStream_t stream, hipEvent_t done);
+hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipStream_t stream,
+                        hipEvent_t start, hipEvent_t stop);
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
 }  // namespace oserve

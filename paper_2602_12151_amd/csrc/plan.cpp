@@ -12,11 +12,11 @@ oserve_status_t SplitPlan::check_geometry(const Geometry& g, int32_t batch, int3
                                           int32_t split_tokens) {
     if (g.num_q_heads < 1 || g.num_kv_heads < 1 || g.num_q_heads % g.num_kv_heads != 0)
         return OSERVE_ERR_SHAPE;
-    if (g.group() > 16) return OSERVE_ERR_SHAPE;
+    if (g.group() > 16 || g.num_kv_heads >= (1 << (31 - kKvHeadShift))) return OSERVE_ERR_SHAPE;
     if (g.head_dim != 64 && g.head_dim != 128) return OSERVE_ERR_SHAPE;
     if (g.page_size != 16) return OSERVE_ERR_SHAPE;
     if (g.max_pages_per_seq < 1 || g.max_pages_per_seq > (1 << 26)) return OSERVE_ERR_SHAPE;
-    if (batch < 1 || capacity < batch || capacity > (1 << 20)) return OSERVE_ERR_SHAPE;
+    if (batch < 1 || capacity < batch || capacity > (1 << kKvHeadShift)) return OSERVE_ERR_SHAPE;
     if (split_tokens < 0 || split_tokens % g.page_size != 0) return OSERVE_ERR_SHAPE;
     return OSERVE_OK;
 }
@@ -36,13 +36,12 @@ int64_t SplitPlan::max_items() const {
 }
 
 WorkspaceLayout SplitPlan::layout(int64_t items, int64_t row_groups, int64_t runs, int32_t n) const {
-    (void)items;
+    (void)runs;
     auto align = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
     WorkspaceLayout w{};
-    w.records_off = 0;
-    w.req_info_off = static_cast<size_t>(runs) * sizeof(RunRecord);
-    w.upload_bytes = w.req_info_off + static_cast<size_t>(n) * sizeof(RequestInfo);
-    w.partial_o_off = align(w.upload_bytes + 16);  // the upload kernel copies whole 16-byte words
+    w.req_info_off = 0;
+    w.items_off = align(static_cast<size_t>(n) * sizeof(RequestInfo) + 16);  // copied in whole 16-byte words
+    w.partial_o_off = w.items_off + align(static_cast<size_t>(items) * sizeof(ItemDesc));
     const size_t rows = static_cast<size_t>(row_groups) * geo.num_q_heads;
     w.partial_ml_off = w.partial_o_off + align(rows * geo.head_dim * sizeof(float));
     w.total = w.partial_ml_off + align(rows * 2 * sizeof(float));
@@ -71,9 +70,9 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     if (c == 0) {
         const int64_t slots = static_cast<int64_t>(num_cus) * kSlotsPerCu;
         const int64_t units = total_pages * geo.num_kv_heads;
-        const int64_t target = slots * tuning.items_per_slot;
+        const int64_t target = std::max<int64_t>(1, slots * tuning.items_per_slot_x4 / 4);
         int64_t want = (units + target - 1) / target;
-        want = std::min<int64_t>(kMaxAutoSplitPages, std::max<int64_t>(kSplitGranule, want));
+        want = std::min<int64_t>(tuning.max_split_pages, std::max<int64_t>(kSplitGranule, want));
         c = round_up(static_cast<int32_t>(want), kSplitGranule);
         // Work is handed out evenly only while an item is no longer than what is left per slot.
         // Full-size items therefore stop when about slots * C page-units are left, and from there
@@ -151,7 +150,11 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     int64_t items = 0;
     for (RunRecord& r : recs) {
         r.first_item = static_cast<int32_t>(items);
-        items += static_cast<int64_t>(r.num_splits) * geo.num_kv_heads;
+        const int64_t run_items = static_cast<int64_t>(r.num_splits) * geo.num_kv_heads;
+        // per-run bound: the device splits an item index into (split, kv head) with a 32-bit
+        // multiply-high that is exact below 2^20
+        if (run_items > (1 << 20)) return OSERVE_ERR_SHAPE;
+        items += run_items;
         if (items > (1 << 30)) return OSERVE_ERR_SHAPE;
     }
     if (row_groups * geo.num_q_heads > (1 << 30)) return OSERVE_ERR_SHAPE;

@@ -9,8 +9,8 @@
 namespace oserve {
 
 // A run = consecutive splits of one request that all have the same size (the very last split of a
-// request may be shorter).  One record per run, in launch order (largest splits first).  Uploaded
-// to the front of the workspace; a wavefront finds its run by binary search over first_item.
+// request may be shorter).  One record per run, in launch order (largest splits first).  The device
+// reads the records from pinned host memory and expands them into one ItemDesc per work item.
 struct RunRecord {
     int32_t request;          // index b into q / block_table / context_lens / out
     int32_t first_item;       // index of the run's first work item; items are (split, kv head), kv head fastest
@@ -23,6 +23,16 @@ struct RunRecord {
 };
 static_assert(sizeof(RunRecord) == 32, "record layout is part of the kernel interface");
 
+// What one wavefront of the split kernel works on; written on the device from the run records.
+struct ItemDesc {
+    int32_t request_kvh;      // request | kv head << kKvHeadShift
+    int32_t page_begin;       // logical pages [page_begin, page_end) of the request
+    int32_t page_end;
+    int32_t row;              // partial-result row group, or -1: the request has one split, write `out`
+};
+static_assert(sizeof(ItemDesc) == 16, "descriptor layout is part of the kernel interface");
+constexpr int32_t kKvHeadShift = 20;       // requests < 2^20, kv heads < 2^11
+
 struct RequestInfo {          // per request, in request order; read by the merge kernel
     int32_t split_base;       // first partial-result row group of the request
     int32_t num_splits;
@@ -34,8 +44,7 @@ struct Geometry {
 };
 
 struct WorkspaceLayout {
-    size_t records_off, req_info_off, partial_o_off, partial_ml_off, total;
-    size_t upload_bytes;      // records + request info are contiguous and uploaded together
+    size_t req_info_off, items_off, partial_o_off, partial_ml_off, total;
 };
 
 // Split sizing constants.  In automatic mode the largest split C is a multiple of kSplitGranule
@@ -49,8 +58,9 @@ constexpr int32_t kMaxRunsPerRequest = 8;
 constexpr int32_t kSlotsPerCu = 4;
 
 struct PlanTuning {
-    int32_t items_per_slot = 3;   // full-size items per wavefront slot
-    int32_t tail_slots_x16 = 8;   // tapered share = this/16 * slots * C page-units (see build())
+    int32_t items_per_slot_x4 = 12;  // full-size items per wavefront slot, in quarters
+    int32_t tail_slots_x16 = 8;      // tapered share = this/16 * slots * C page-units (see build())
+    int32_t max_split_pages = kMaxAutoSplitPages;
 };
 
 // Pure host logic (no HIP): everything the CPU tests exercise.
