@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the split kernel (read + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # scaled by a plain copy of known size: profiles/split_kernel_cfg3_heterogeneous_mix.md.  Only the
 # workload that was profiled has an entry; the others report null.
-MEASURED_TRAFFIC_BYTES = {3: 6_955_500_000 + 14_200_000}
+MEASURED_TRAFFIC_BYTES = {3: 6_959_823_667 + 10_751_590}
 
 
 def parse_args():

@@ -22,7 +22,7 @@
  * computed on the caller's stream by a split kernel (one wavefront per
  * (request, kv head, sequence split), online softmax, fp32 accumulation, bf16
  * MFMA) and a log-sum-exp merge of the splits; a third, tiny kernel first
- * copies the plan's records into the workspace.
+ * expands the plan's records into one descriptor per work item in the workspace.
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless its name ends in _host; `plan`
@@ -69,12 +69,13 @@ typedef enum {
  * explicit `split_tokens` the sequence of request b (N_b pages) is cut into
  * S_b = ceil(N_b / C) splits of ceil(N_b / S_b) pages, C = split_tokens /
  * page_size.  With `split_tokens` = 0 the planner picks C (a multiple of 12
- * pages) so that the batch yields a few full-size work items per resident
- * wavefront of the device, requests of at most C pages stay whole, and longer
- * ones are cut into full-size splits followed by a tail of splits that shrink
- * (C, C/2, C/4, ... 12 pages) in proportion to what is left of the request.
- * Work items (request, kv head, split) are launched largest split first, so
- * the small ones fill the end of the launch.  Host-only, O(batch log batch).
+ * pages) as one resident wavefront's fair share of the batch (pages of the
+ * batch x kv heads / wavefront slots of the device); requests of at most C
+ * pages stay whole, and longer ones are cut into full-size splits followed by
+ * a tail of splits that shrink (C, C/2, C/4, ... 12 pages) in proportion to
+ * what is left of the request.  Work items (request, kv head, split) are
+ * launched largest split first, so the small ones fill the end of the launch.
+ * Host-only, O(batch log batch).
  *
  *   context_lens_host  [batch] int32, host memory, each in [1, max_pages_per_seq*page_size]
  *   max_pages_per_seq  row stride (entries) of the block table passed at launch
@@ -123,9 +124,9 @@ size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);
 
 /*
  * One decode step of paged attention (definition at the top of this file).
- * Enqueues on `stream`: a one-workgroup kernel that copies the plan's records
- * from pinned host memory into `workspace`, the split kernel, and (if any
- * request is split) the merge kernel.  Returns without waiting.  The records
+ * Enqueues on `stream`: a one-workgroup kernel that reads the plan's records
+ * from pinned host memory and writes the work-item descriptors into
+ * `workspace`, the split kernel, and (if any request is split) the merge kernel.  Returns without waiting.  The records
  * are staged at call time, so the plan may be updated as soon as the call
  * returns; it must not be destroyed before the launch has run.
  *
@@ -158,7 +159,8 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
 
 /*
  * Optional timing of the split kernel alone.  When enabled, each launch
- * brackets the split kernel with HIP events on the launch stream.
+ * attaches a begin and an end HIP event to the split kernel's dispatch on the
+ * launch stream.
  * oserve_plan_split_kernel_ms waits for the launches recorded so far and
  * returns the mean split-kernel duration in milliseconds over all launches
  * since timing was enabled (enabling again resets the mean), and their count.

@@ -97,7 +97,7 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
                               static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo) + 16 + 255) & ~static_cast<size_t>(255);
     if (const char* e = getenv("OSERVE_PLAN_TUNING")) {  // experiments: "items_per_slot_x4,tail_slots_x16,max_split_pages"
         int a = 0, b = 0, c = 0;
-        if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && a > 0 && b >= 0 && c >= 12 && c <= 4096)
+        if (sscanf(e, "%d,%d,%d", &a, &b, &c) == 3 && a > 0 && b >= 0 && c >= 12)
             pl->host.tuning = oserve::PlanTuning{a, b, c};
     }
     pl->device_id = device_id;

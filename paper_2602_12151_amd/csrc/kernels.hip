@@ -390,7 +390,7 @@ namespace {
 struct Variant { int nbuf, wpe; };
 
 Variant chosen_variant() {
-    Variant d{3, 1};
+    Variant d{2, 1};
     if (const char* e = getenv("OSERVE_VARIANT")) {
         int a = 0, b = 0;
         if (sscanf(e, "%d,%d", &a, &b) == 2) d = Variant{a, b};

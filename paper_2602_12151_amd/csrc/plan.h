@@ -47,20 +47,22 @@ struct WorkspaceLayout {
     size_t req_info_off, items_off, partial_o_off, partial_ml_off, total;
 };
 
-// Split sizing constants.  In automatic mode the largest split C is a multiple of kSplitGranule
-// chosen so that the batch yields about kItemsPerSlot full-size items per wavefront slot
-// (kSlotsPerCu per compute unit); the end of every long request is cut into smaller splits taken
-// from the ladder C, C/2, C/4, ... >= kSplitGranule (each rounded up to the granule), so a request
-// contributes at most kMaxRunsPerRequest runs.
+// Split sizing.  In automatic mode the largest split C is one wavefront slot's fair share of the
+// batch: (page-units of the batch) / (wavefront slots of the device), rounded up to a multiple of
+// kSplitGranule pages, so the first, largest items fill every slot once and no slot ever holds two
+// of them.  The end of every long request is cut into smaller splits taken from the ladder
+// C, C/2, C/4, ... >= kSplitGranule (each rounded up to the granule); a request contributes at most
+// kMaxRunsPerRequest runs.  Measured on the five workloads and modelled over scaled variants of
+// them, whole multiples or fractions of the fair share other than 1 leave slots idle at the end
+// (up to 20 % longer launches), so items_per_slot_x4 should stay 4.
 constexpr int32_t kSplitGranule = 12;
-constexpr int32_t kMaxAutoSplitPages = 384;
 constexpr int32_t kMaxRunsPerRequest = 8;
 constexpr int32_t kSlotsPerCu = 4;
 
 struct PlanTuning {
-    int32_t items_per_slot_x4 = 12;  // full-size items per wavefront slot, in quarters
-    int32_t tail_slots_x16 = 8;      // tapered share = this/16 * slots * C page-units (see build())
-    int32_t max_split_pages = kMaxAutoSplitPages;
+    int32_t items_per_slot_x4 = 4;   // full-size items per wavefront slot, in quarters
+    int32_t tail_slots_x16 = 6;      // tapered share = this/16 * slots * C page-units (see build())
+    int32_t max_split_pages = 1 << 26;  // optional cap on C (none by default)
 };
 
 // Pure host logic (no HIP): everything the CPU tests exercise.
