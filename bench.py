@@ -35,7 +35,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload index 0..4 (default: the heterogeneous mix)")
+    ap.add_argument("--config", type=int, default=3, help="workload index: 0..4 are the five benchmark configs (default 3, the heterogeneous mix), "
+                         "5..8 shape variants of the mix (MHA shard, 8q/1kv shard, pages of 32 and 64 tokens)")
     ap.add_argument("--split-tokens", type=int, default=0, help="0 = automatic split sizing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
@@ -175,7 +176,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg{w.index} {w.name}: batch {w.batch}, {w.num_q_heads}q/{w.num_kv_heads}kv heads, "
-                               f"head_dim {w.head_dim}, page 16, {int(sets[0].context_lens_host.sum())} tokens, "
+                               f"head_dim {w.head_dim}, page {w.page_size}, {int(sets[0].context_lens_host.sum())} tokens, "
                                f"{nbytes / 1e9:.3f} GB K+V per step",
                    "work_items": plan0.num_work_items, "split_pages": plan0.split_pages,
                    "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms / args.steps, 5),

@@ -60,8 +60,10 @@ typedef enum {
 /* Launches a plan may have in flight before a launch call waits for the oldest. */
 #define OSERVE_PLAN_RING 8
 
-/* Supported shapes: head_dim 64 or 128; page_size 16; num_q_heads a multiple of
- * num_kv_heads with group size num_q_heads / num_kv_heads <= 16. */
+/* Supported shapes: head_dim 64 or 128; page_size 16, 32 or 64; num_q_heads a
+ * multiple of num_kv_heads with group size num_q_heads / num_kv_heads <= 16.
+ * Split sizes are counted in tiles of 16 tokens (a page holds 1, 2 or 4 tiles), so
+ * "pages" in the plan queries below means tiles; the two coincide at page_size 16. */
 
 /*
  * Plan: sizes the sequence splits of one batch from its context lengths (the
@@ -134,7 +136,8 @@ size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);
  *                  contents are scratch.  Two launches that overlap in time must
  *                  not share a workspace.
  *   q              bf16 [batch, num_q_heads, head_dim], contiguous
- *   k_pages        bf16 [num_pages, num_kv_heads, page_size, head_dim], contiguous,
+ *   k_pages        bf16 [num_pages, num_kv_heads, page_size, head_dim], contiguous (the tiles of a page follow
+ *                  each other),
  *   v_pages        same shape; 16-byte aligned.  Slots at or beyond a request's context
  *                  length (in its last page) may be read but never influence the result,
  *                  whatever they hold; pages no table row names are never read.

@@ -91,7 +91,7 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
     if (!pl) return OSERVE_ERR_DEVICE;
     pl->host.geo = geo;
     pl->host.capacity = capacity;
-    pl->host.split_pages_user = split_tokens / page_size;
+    pl->host.split_pages_user = split_tokens / oserve::kTileTokens;
     pl->host.reserve();
     pl->staging_slot_bytes = (static_cast<size_t>(pl->host.max_runs()) * sizeof(RunRecord) +
                               static_cast<size_t>(capacity) * sizeof(oserve::RequestInfo) + 16 + 255) & ~static_cast<size_t>(255);
@@ -240,6 +240,7 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
     sp.num_kv_heads = hp.geo.num_kv_heads;
     sp.group = hp.geo.group();
     sp.max_pages_per_seq = hp.geo.max_pages_per_seq;
+    sp.tile_shift = hp.geo.page_size == 64 ? 2 : hp.geo.page_size == 32 ? 1 : 0;
 
     if (oserve::launch_split(sp, hp.geo.head_dim, hp.num_items, stream,
                              plan->timing ? plan->t_begin[slot] : nullptr,

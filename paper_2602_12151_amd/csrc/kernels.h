@@ -11,7 +11,7 @@ namespace oserve {
 struct SplitParams {
     const ItemDesc* items;         // one per work item, launch order
     const uint16_t* q;             // bf16 bits [B, Hq, D]
-    const uint16_t* k_pages;       // bf16 bits [P, Hkv, 16, D]
+    const uint16_t* k_pages;       // bf16 bits [P, Hkv, page_size, D]
     const uint16_t* v_pages;
     const int32_t* block_table;    // [B, max_pages_per_seq]
     const int32_t* context_lens;   // [B]
@@ -20,6 +20,7 @@ struct SplitParams {
     float* partial_ml;             // [row_groups * Hq, 2]: running max (log2 domain), normaliser
     float scale_log2e;             // scale * log2(e)
     int32_t num_q_heads, num_kv_heads, group, max_pages_per_seq;
+    int32_t tile_shift;            // log2(page_size / 16): 16-token tiles per page
 };
 
 struct MergeParams {

@@ -139,23 +139,26 @@ void paged_decode_split_kernel(const SplitParams p) {
         }
     }
 
-    // ---- physical page ids: wave-uniform (scalar) loads, fetched one step before they are needed ----
+    // ---- where each 16-token tile lives: wave-uniform (scalar) block-table loads, fetched one step
+    // before they are needed.  A page holds 1 << tile_shift tiles, one after the other.
     const int32_t* bt_row = p.block_table + static_cast<int64_t>(b) * p.max_pages_per_seq;
     const int last_page = pend - 1;
-    auto page_id_of = [&](int pg) -> int {  // clamped: never reads a table entry the request does not own
-        return __builtin_amdgcn_readfirstlane(bt_row[min(pg, last_page)]);
+    const int tile_mask = (1 << p.tile_shift) - 1;
+    const int64_t page_elems = (static_cast<int64_t>(p.num_kv_heads) * PAGE * D) << p.tile_shift;
+    const int64_t head_off = (static_cast<int64_t>(kvh) * PAGE * D) << p.tile_shift;
+    auto tile_base_of = [&](int pg) -> int64_t {  // clamped: never reads a table entry the request does not own
+        const int t = min(pg, last_page);
+        const int pid = __builtin_amdgcn_readfirstlane(bt_row[t >> p.tile_shift]);
+        return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (PAGE * D);
     };
 
-    const int64_t page_elems = static_cast<int64_t>(p.num_kv_heads) * PAGE * D;
-    const int64_t head_off = static_cast<int64_t>(kvh) * PAGE * D;
     const int k_lane_off = i16 * D + g4 * 8;         // + 32*kk elements
     const int v_lane_off = (4 * g4) * D + EV * i16;  // + c*D elements
 
     uint4 kbuf[NBUF][KK];
     uint32_t vbuf[NBUF][4][VW];
 
-    auto issue = [&](int slot, int pid) {
-        const int64_t base = static_cast<int64_t>(pid) * page_elems + head_off;
+    auto issue = [&](int slot, int64_t base) {
         const uint16_t* kp = p.k_pages + base + k_lane_off;
         const uint16_t* vp = p.v_pages + base + v_lane_off;
 #pragma unroll
@@ -258,12 +261,12 @@ void paged_decode_split_kernel(const SplitParams p) {
     // Steady state issues the loads of page pg+NBUF-1 unconditionally before consuming page pg, so
     // the only wait is for the oldest page; the last NBUF-1 pages are drained without new loads.
     // An item shorter than NBUF-1 pages re-loads its last page in the prologue (harmless).
-    int pid_ring[NBUF];
+    int64_t base_ring[NBUF];
 #pragma unroll
-    for (int u = 0; u < NBUF; ++u) pid_ring[u] = page_id_of(pbeg + u);
+    for (int u = 0; u < NBUF; ++u) base_ring[u] = tile_base_of(pbeg + u);
 #pragma unroll
-    for (int u = 0; u < NBUF - 1; ++u) issue(u, pid_ring[u]);
-    int next_pid = pid_ring[NBUF - 1];
+    for (int u = 0; u < NBUF - 1; ++u) issue(u, base_ring[u]);
+    int64_t next_base = base_ring[NBUF - 1];
 
     // The device copy of the length only decides how much of the page it falls in counts: a value
     // that disagrees with the plan is clamped into the last page this item owns.  It is fetched
@@ -290,8 +293,8 @@ void paged_decode_split_kernel(const SplitParams p) {
         for (int u = 0; u < NBUF; ++u) {
             if (more) {
                 if (pg < main_end) {
-                    issue((u + NBUF - 1) % NBUF, next_pid);
-                    next_pid = page_id_of(pg + NBUF);
+                    issue((u + NBUF - 1) % NBUF, next_base);
+                    next_base = tile_base_of(pg + NBUF);
                     consume(u, pg, Full{});  // the ragged page, if any, is the item's last: never here
                     ++pg;
                 } else {

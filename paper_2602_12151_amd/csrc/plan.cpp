@@ -14,8 +14,8 @@ oserve_status_t SplitPlan::check_geometry(const Geometry& g, int32_t batch, int3
         return OSERVE_ERR_SHAPE;
     if (g.group() > 16 || g.num_kv_heads >= (1 << (31 - kKvHeadShift))) return OSERVE_ERR_SHAPE;
     if (g.head_dim != 64 && g.head_dim != 128) return OSERVE_ERR_SHAPE;
-    if (g.page_size != 16) return OSERVE_ERR_SHAPE;
-    if (g.max_pages_per_seq < 1 || g.max_pages_per_seq > (1 << 26)) return OSERVE_ERR_SHAPE;
+    if (g.page_size != 16 && g.page_size != 32 && g.page_size != 64) return OSERVE_ERR_SHAPE;
+    if (g.max_pages_per_seq < 1 || g.max_tiles_per_seq() > (1 << 26)) return OSERVE_ERR_SHAPE;
     if (batch < 1 || capacity < batch || capacity > (1 << kKvHeadShift)) return OSERVE_ERR_SHAPE;
     if (split_tokens < 0 || split_tokens % g.page_size != 0) return OSERVE_ERR_SHAPE;
     return OSERVE_OK;
@@ -31,7 +31,7 @@ void SplitPlan::reserve() {
 int64_t SplitPlan::max_items() const {
     // the smallest split the plan can choose bounds the item count from above
     const int64_t c_min = split_pages_user > 0 ? split_pages_user : kSplitGranule;
-    const int64_t per_req = (static_cast<int64_t>(geo.max_pages_per_seq) + c_min - 1) / c_min + kMaxRunsPerRequest;
+    const int64_t per_req = (geo.max_tiles_per_seq() + c_min - 1) / c_min + kMaxRunsPerRequest;
     return per_req * capacity * geo.num_kv_heads;
 }
 
@@ -61,7 +61,7 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     int64_t total_pages = 0;
     for (int32_t b = 0; b < n; ++b) {
         if (lens[b] < 1 || lens[b] > max_len) return OSERVE_ERR_CONTEXT_LEN;
-        total_pages += (lens[b] + geo.page_size - 1) / geo.page_size;
+        total_pages += (lens[b] + kTileTokens - 1) / kTileTokens;
     }
 
     // ---- size of the largest split, and the share of each long request that is tapered ----
@@ -96,7 +96,7 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     info.resize(static_cast<size_t>(n));
     int64_t row_groups = 0;
     for (int32_t b = 0; b < n; ++b) {
-        const int32_t pages = (lens[b] + geo.page_size - 1) / geo.page_size;
+        const int32_t pages = (lens[b] + kTileTokens - 1) / kTileTokens;
         const size_t first_rec = recs.size();
         int32_t splits = 0;
         auto add_run = [&](int32_t begin, int32_t count, int32_t pps, int32_t end) {

@@ -38,9 +38,16 @@ struct RequestInfo {          // per request, in request order; read by the merg
     int32_t num_splits;
 };
 
+// The planner and the kernels work in tiles of kTileTokens tokens (one MFMA tile of keys); a page of
+// the cache holds 1, 2 or 4 of them.  Wherever this code says "pages" of a split, a run or an item
+// it counts tiles; the two coincide at the page size of 16.
+constexpr int32_t kTileTokens = 16;
+
 struct Geometry {
     int32_t num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq;
     int32_t group() const { return num_q_heads / num_kv_heads; }
+    int32_t tiles_per_page() const { return page_size / kTileTokens; }
+    int64_t max_tiles_per_seq() const { return static_cast<int64_t>(max_pages_per_seq) * tiles_per_page(); }
 };
 
 struct WorkspaceLayout {

@@ -103,6 +103,8 @@ class Workload:
     # pool sizing: either a factor over the pages needed, or a fixed page count
     pool_factor: float = 1.25
     pool_pages_fixed: Optional[int] = None
+    # which config's context-length recipe to draw from (None: the workload's own index)
+    recipe: Optional[int] = None
 
     @property
     def group(self) -> int:
@@ -126,26 +128,34 @@ WORKLOADS = (
     Workload(3, "heterogeneous-mix", batch=256, num_q_heads=32, num_kv_heads=8, head_dim=128),
     Workload(4, "long-context", batch=16, num_q_heads=32, num_kv_heads=8, head_dim=128,
              pool_pages_fixed=1 << 21),
+    # Shape variants of the heterogeneous mix: per-GPU head geometries of the paper's other models
+    # (section 6.1: OPT-30B is MHA with 56 heads, Llama2-70B has 64 query / 8 kv heads) at
+    # tensor-parallel degrees its deployments use, and larger cache pages.
+    Workload(5, "mix-opt30b-tp2-mha", batch=128, num_q_heads=28, num_kv_heads=28, head_dim=128, recipe=3),
+    Workload(6, "mix-llama2-70b-tp8", batch=256, num_q_heads=8, num_kv_heads=1, head_dim=128, recipe=3),
+    Workload(7, "mix-page32", batch=256, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=32, recipe=3),
+    Workload(8, "mix-page64", batch=256, num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=64, recipe=3),
 )
 
 
 def context_lens(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     """int32 [batch] context lengths of workload `w` (the recipe of each config)."""
     rng = CounterRng(w.seed if seed is None else seed)
-    if w.index == 0:
+    recipe = w.index if w.recipe is None else w.recipe
+    if recipe == 0:
         lens = np.array([17, 64, 200, 513], dtype=np.int64)
-    elif w.index == 1:
+    elif recipe == 1:
         lens = rng.integers(128, 2048, w.batch)
-    elif w.index == 2:
+    elif recipe == 2:
         lens = rng.integers(1024, 16384, w.batch)
-    elif w.index == 3:
+    elif recipe == 3:
         n_short = int(round(0.7 * w.batch))
         n_long = w.batch - n_short
         z = rng.normal(n_short)
         short = np.clip(np.rint(np.exp(math.log(512.0) + 0.8 * z)), 16, 4096).astype(np.int64)
         long_ = rng.integers(8192, 32768, n_long)
         lens = np.concatenate([short, long_])[rng.permutation(w.batch)]
-    elif w.index == 4:
+    elif recipe == 4:
         lens = rng.integers(65536, 131072, w.batch)
     else:
         raise ValueError(f"unknown workload {w.index}")
@@ -239,7 +249,7 @@ def make_inputs(w: Workload, device="cpu", seed: Optional[int] = None,
     rng = CounterRng(seed ^ 0x5EED)
     if pool_pages_override is not None:
         npool = pool_pages_override
-    elif w.pool_pages_fixed is not None and int(pages_needed(lens).sum()) <= w.pool_pages_fixed:
+    elif w.pool_pages_fixed is not None and int(pages_needed(lens, w.page_size).sum()) <= w.pool_pages_fixed:
         npool = w.pool_pages_fixed
     else:
         npool = int(math.ceil(w.pool_factor * int(pages_needed(lens, w.page_size).sum())))

@@ -76,6 +76,41 @@ def test_mha_and_group_sizes():
         gh.assert_parity(out, gh.oracle_attention(cpu), f"hq={hq} hkv={hkv} d={d}")
 
 
+@pytest.mark.parametrize("page_size", [32, 64])
+@pytest.mark.parametrize("hq,hkv,d", [(32, 8, 128), (8, 2, 64), (7, 7, 128)])
+def test_page_sizes_32_and_64(page_size, hq, hkv, d):
+    """Pages of 2 and 4 key tiles: lengths around tile and page boundaries, splits that start inside a
+    page, NaN in every dead slot of the last pages."""
+    lens = np.array([1, 16, 17, 31, 33, 63, 64, 65, 127, 129, 700, 1291, 4000], dtype=np.int32)
+    w = wl.Workload(9, "pages", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=d, page_size=page_size)
+    cpu = wl.make_inputs(w, device="cpu", seed=page_size + hq, lens=lens)
+    bt = cpu.block_table.numpy()
+    for b, L in enumerate(lens):
+        if L % page_size:
+            last = int(bt[b, (L - 1) // page_size])
+            cpu.k_pages[last, :, L % page_size:, :] = float("nan")
+            cpu.v_pages[last, :, L % page_size:, :] = float("nan")
+    dev = gh.to_device(cpu)
+    ref = gh.oracle_attention(cpu)
+    for split_tokens in (0, page_size, 3 * page_size, 1024):
+        out, _ = gh.gpu_attention(dev, split_tokens=split_tokens)
+        gh.assert_parity(out, ref, f"page={page_size} hq={hq} hkv={hkv} d={d} split={split_tokens}")
+
+
+@pytest.mark.parametrize("name,hq,hkv", [("OPT-30B (MHA, 56 heads) TP=2", 28, 28), ("OPT-66B (MHA, 72 heads) TP=4", 18, 18),
+                                         ("Llama-30B (MHA, 52 heads) TP=4", 13, 13), ("Llama2-70B TP=2", 32, 4),
+                                         ("Llama2-70B TP=8", 8, 1), ("Llama2-70B TP=1", 64, 8)])
+def test_head_geometries_of_the_papers_models(name, hq, hkv):
+    """Per-GPU head counts of the models of section 6.1 at tensor-parallel degrees its deployments use
+    (all head_dim 128), on a small mixed-length batch."""
+    lens = np.array([40, 2100, 517, 9000, 16, 1300], dtype=np.int32)
+    w = wl.Workload(9, name, batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=128)
+    cpu = wl.make_inputs(w, device="cpu", seed=hq * 7 + hkv, lens=lens)
+    dev = gh.to_device(cpu)
+    out, _ = gh.gpu_attention(dev)
+    gh.assert_parity(out, gh.oracle_attention(cpu), name)
+
+
 def test_unread_memory_is_poisoned_with_nan():
     """NaN in tail slots of last pages and in every page no table row names must not reach the output."""
     lens = [1, 15, 17, 100, 513, 1030]

@@ -6,10 +6,10 @@ import pytest
 from paper_2602_12151_amd import binding, workloads as wl
 
 
-def make_plan(lens, hq=32, hkv=8, d=128, split_tokens=0, capacity=None):
+def make_plan(lens, hq=32, hkv=8, d=128, split_tokens=0, capacity=None, page_size=16):
     lens = np.asarray(lens, dtype=np.int32)
-    width = int(wl.pages_needed(lens).max())
-    return binding.Plan(lens, hq, hkv, d, 16, width, split_tokens, -1, capacity)
+    width = int(wl.pages_needed(lens, page_size).max())
+    return binding.Plan(lens, hq, hkv, d, page_size, width, split_tokens, -1, capacity)
 
 
 def check_plan(plan, lens, hkv):
@@ -68,6 +68,21 @@ def test_explicit_split_size(split_tokens):
         assert plan.request(b)[0] == -(-pages // pps)      # near-equal splits
 
 
+@pytest.mark.parametrize("page_size", [32, 64])
+def test_larger_pages_are_planned_in_tiles_of_16_tokens(page_size):
+    """With pages of 32 or 64 tokens the plan still counts 16-token tiles: same splits as for page 16."""
+    lens = wl.context_lens(wl.WORKLOADS[3])
+    ref = make_plan(lens)
+    plan = make_plan(lens, page_size=page_size)
+    check_plan(plan, lens, 8)
+    assert plan.num_runs == ref.num_runs and plan.num_work_items == ref.num_work_items
+    for i in range(plan.num_runs):
+        assert plan.run(i) == ref.run(i)
+    explicit = make_plan([1, 33, 1000, 33000], split_tokens=3 * page_size, page_size=page_size)
+    check_plan(explicit, [1, 33, 1000, 33000], 8)
+    assert explicit.split_pages == 3 * page_size // 16
+
+
 def test_tapered_tail_of_a_long_request():
     """In automatic mode a long request ends in splits that shrink down to the granule."""
     w = wl.WORKLOADS[3]
@@ -105,7 +120,10 @@ def test_create_rejects_bad_shapes():
         dict(num_q_heads=30, num_kv_heads=8),       # not a multiple
         dict(num_q_heads=64, num_kv_heads=2),       # group 32 > 16
         dict(head_dim=96),
-        dict(page_size=32),
+        dict(page_size=8),
+        dict(page_size=48),
+        dict(page_size=128),
+        dict(page_size=32, split_tokens=48),        # not a multiple of the page size
         dict(split_tokens=40),                      # not a multiple of the page size
     ]
     for kw in bad:
