@@ -1,4 +1,5 @@
-// CPU oracle for paged GQA decode attention.  TEST INFRASTRUCTURE ONLY.
+// CPU oracle for paged GQA decode attention (and its causal, several-queries-per-request form,
+// chunked prefill, at the end of this file).  TEST INFRASTRUCTURE ONLY.
 //
 // This file is the slow, plain, fp64 statement of what one decode step of
 // attention over a paged KV cache computes.  It exists so that the GPU library
@@ -34,7 +35,11 @@
 // dominant key selects its value row; an independent dense (unpaged) numpy
 // softmax(QK^T*scale)V agrees to 1e-12 on tiny inputs; merging per-part
 // results by their log-sum-exp reproduces the unsplit result; poisoning unread
-// slots with NaN changes nothing.  No part of this oracle is unpinned.
+// slots with NaN changes nothing.  The prefill form is pinned by: one query per request
+// reproduces the decode oracle bit for bit; every query row equals the decode oracle on the
+// context cut after its own position; an independent dense masked softmax in numpy long doubles;
+// the first token of a whole prompt returns v_0; changing a later token changes no earlier row.
+// No part of this oracle is unpinned.
 
 #include <cmath>
 #include <cstdint>
@@ -56,12 +61,12 @@ struct Layout {
     int64_t bt_stride;                              // block_table row stride (entries)
 };
 
-// One (request, query head).  Returns 0, or a negative code on a bad table entry.
-int attend_one(const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
+// One query row (q_row: head_dim bf16 values) of request b over its first L cached tokens.
+// Returns 0, or a negative code on a bad table entry.
+int attend_row(const uint16_t* q_row, const uint16_t* k_pool, const uint16_t* v_pool,
                const int32_t* block_table, const Layout& lay, int64_t num_pool_pages,
-               int b, int h, int kv_head, int L, int head_dim, int page_size,
+               int b, int kv_head, int L, int head_dim, int page_size,
                double scale, double* out_row, double* lse_out) {
-    const uint16_t* q_row = q + b * lay.q_stride_b + h * lay.q_stride_h;
     std::vector<double> s(static_cast<size_t>(L));
 
     // pass 1: scores and their maximum
@@ -117,7 +122,8 @@ int oserve_oracle_paged_decode_attn(
         for (int h = 0; h < num_q_heads; ++h) {
             double* out_row = out + (static_cast<int64_t>(b) * num_q_heads + h) * head_dim;
             double* lse_p = lse ? lse + static_cast<int64_t>(b) * num_q_heads + h : nullptr;
-            int rc = attend_one(q, k_pool, v_pool, block_table, lay, num_pool_pages, b, h, h / group, L,
+            const uint16_t* q_row = q + b * lay.q_stride_b + h * lay.q_stride_h;
+            int rc = attend_row(q_row, k_pool, v_pool, block_table, lay, num_pool_pages, b, h / group, L,
                                 head_dim, page_size, static_cast<double>(scale), out_row, lse_p);
             if (rc != 0) return 3;
         }
@@ -138,10 +144,52 @@ int oserve_oracle_one_head(
     const int L = context_lens[b];
     if (L < 1) return 2;
     const Layout lay{q_stride_b, q_stride_h, kv_stride_page, kv_stride_head, kv_stride_tok, bt_stride};
-    int rc = attend_one(q, k_pool, v_pool, block_table, lay, num_pool_pages, b, h,
-                        h / (num_q_heads / num_kv_heads), L, head_dim, page_size,
+    int rc = attend_row(q + b * lay.q_stride_b + h * lay.q_stride_h, k_pool, v_pool, block_table, lay,
+                        num_pool_pages, b, h / (num_q_heads / num_kv_heads), L, head_dim, page_size,
                         static_cast<double>(scale), out_row, lse);
     return rc != 0 ? 3 : 0;
+}
+
+// Chunked prefill over the same paged cache (paper section 2: the prefill phase processes the
+// prompt's tokens in parallel and is compute-bound; a chunk of it, or a whole prompt, attends
+// causally).  Request b brings n = q_lens[b] new query tokens whose keys and values are already
+// the last n of its L = context_lens[b] cached tokens.  Query token i (0 <= i < n) sits at
+// position p = L - n + i and attends to the cached tokens 0..p, nothing later:
+//
+//     out[q_start_b + i][h][:] = sum_{t <= p} softmax_{t <= p}(scale * <q_i, k_t>) * v_t
+//
+// with q_start_b = q_lens[0] + ... + q_lens[b-1] (queries of all requests packed one after the
+// other).  n = 1 is the decode step above.  q: bf16 [sum n, num_q_heads, head_dim] by strides;
+// out: double [sum n, num_q_heads, head_dim] contiguous.  Returns 0; 1 bad shape; 2 a length < 1 or
+// n > L; 3 block-table entry outside the pool.
+int oserve_oracle_paged_prefill_attn(
+        const uint16_t* q, int64_t q_stride_tok, int64_t q_stride_h,
+        const uint16_t* k_pool, const uint16_t* v_pool, int64_t num_pool_pages,
+        int64_t kv_stride_page, int64_t kv_stride_head, int64_t kv_stride_tok,
+        const int32_t* block_table, int64_t bt_stride, const int32_t* context_lens,
+        const int32_t* q_lens, int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
+        int32_t head_dim, int32_t page_size, float scale, double* out) {
+    if (batch < 0 || num_q_heads < 1 || num_kv_heads < 1 || head_dim < 1 || page_size < 1) return 1;
+    if (num_q_heads % num_kv_heads != 0) return 1;
+    const int group = num_q_heads / num_kv_heads;
+    const Layout lay{q_stride_tok, q_stride_h, kv_stride_page, kv_stride_head, kv_stride_tok, bt_stride};
+    int64_t row = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int L = context_lens[b];
+        const int n = q_lens[b];
+        if (L < 1 || n < 1 || n > L) return 2;
+        for (int i = 0; i < n; ++i, ++row) {
+            const int visible = L - n + i + 1;   // tokens 0..p
+            for (int h = 0; h < num_q_heads; ++h) {
+                const uint16_t* q_row = q + row * lay.q_stride_b + h * lay.q_stride_h;
+                double* out_row = out + (row * num_q_heads + h) * head_dim;
+                int rc = attend_row(q_row, k_pool, v_pool, block_table, lay, num_pool_pages, b, h / group,
+                                    visible, head_dim, page_size, static_cast<double>(scale), out_row, nullptr);
+                if (rc != 0) return 3;
+            }
+        }
+    }
+    return 0;
 }
 
 }  // extern "C"

@@ -42,6 +42,10 @@ def _load():
         lib.oserve_oracle_one_head.argtypes = [
             vp, i64, i64, vp, vp, i64, i64, i64, i64, vp, i64, vp,
             i32, i32, i32, i32, ctypes.c_float, i32, i32, vp, vp]
+        lib.oserve_oracle_paged_prefill_attn.restype = ctypes.c_int
+        lib.oserve_oracle_paged_prefill_attn.argtypes = [
+            vp, i64, i64, vp, vp, i64, i64, i64, i64, vp, i64, vp, vp,
+            i32, i32, i32, i32, i32, ctypes.c_float, vp]
         _lib = lib
     return _lib
 
@@ -122,6 +126,34 @@ def one_head(q, k_pages, v_pages, block_table, context_lens, scale: float, b: in
         qb.ctypes.data, qs[0], qs[1], kb.ctypes.data, vb.ctypes.data, P, ks[0], ks[1], ks[2],
         bt.ctypes.data, _elem_strides(bt)[0], cl.ctypes.data, Hq, Hkv, D, page,
         ctypes.c_float(scale), b, h, out.ctypes.data, None)
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return out
+
+
+def paged_prefill_attn(q, k_pages, v_pages, block_table, context_lens, q_lens, scale: float):
+    """Causal chunked-prefill oracle: q is [sum(q_lens), Hq, D] (requests packed), output double of that shape."""
+    lib = _load()
+    qb, kb, vb = _bits(q), _bits(k_pages), _bits(v_pages)
+    bt, cl, ql = _i32(block_table), _i32(context_lens), _i32(q_lens)
+    _check_kv(kb, vb)
+    T, Hq, D = qb.shape
+    P, Hkv, page, Dk = kb.shape
+    B = cl.shape[0]
+    if Dk != D or _elem_strides(qb)[2] != 1 or bt.ndim != 2 or bt.shape[0] != B or ql.shape != (B,):
+        raise ValueError("shape mismatch")
+    if int(ql.sum()) != T:
+        raise ValueError("q_lens must add up to the number of query rows")
+    if not cl.flags.c_contiguous or not ql.flags.c_contiguous or _elem_strides(bt)[1] != 1:
+        raise ValueError("context_lens / q_lens / block_table rows must be contiguous")
+    if B and int(cl.max()) > bt.shape[1] * page:
+        raise ValueError("context length exceeds block table width")
+    out = np.empty((T, Hq, D), dtype=np.float64)
+    qs, ks = _elem_strides(qb), _elem_strides(kb)
+    rc = lib.oserve_oracle_paged_prefill_attn(
+        qb.ctypes.data, qs[0], qs[1], kb.ctypes.data, vb.ctypes.data, P, ks[0], ks[1], ks[2],
+        bt.ctypes.data, _elem_strides(bt)[0], cl.ctypes.data, ql.ctypes.data, B, Hq, Hkv, D, page,
+        ctypes.c_float(scale), out.ctypes.data)
     if rc != 0:
         raise ValueError(f"oracle rejected its input (code {rc})")
     return out
