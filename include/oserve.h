@@ -173,6 +173,80 @@ oserve_status_t oserve_plan_split_kernel_ms(oserve_plan_t* plan, float* mean_ms,
 
 const char* oserve_status_string(oserve_status_t status);
 
+/* ---------------------------------------------------------------------------
+ * Chunked prefill over the same paged cache: the compute-bound side of the
+ * batch (paper section 2, "Phases of LLM inference": the prefill phase
+ * processes the prompt's tokens in parallel; section 1 (i): short requests are
+ * compute-bound, long ones memory-bound).  Request b brings n_b = q_lens[b] new
+ * query tokens whose keys and values already are the last n_b of its
+ * L_b = context_lens[b] cached tokens.  Query token i (0 <= i < n_b) sits at
+ * position p = L_b - n_b + i and attends causally:
+ *
+ *     out[r_b + i][h][:] = sum_{t <= p} softmax_{t <= p}(scale * <q[r_b + i][h], k_t>) * v_t
+ *
+ * with r_b = q_lens[0] + ... + q_lens[b-1] (the queries of all requests packed one
+ * after the other), kv head and k_t, v_t as for the decode call.  n_b = 1 is a
+ * decode step; a whole prompt is n_b = L_b.  A mixed batch is served by running
+ * its decode requests through oserve_paged_decode_attn and its prefill chunks
+ * through this call on the same stream.
+ *
+ * One workgroup of four wavefronts handles a block of 256 / G query tokens of one
+ * request against one kv head (G = num_q_heads / num_kv_heads); K and V tiles go
+ * through LDS; both products run on bf16 MFMA with fp32 accumulation; the
+ * probabilities are rounded to bf16 for the second product.
+ * Supported shapes: head_dim 128; page_size 16, 32 or 64; G in {1, 2, 4, 8, 16}.
+ * ------------------------------------------------------------------------- */
+typedef struct oserve_prefill_plan oserve_prefill_plan_t;
+
+/*
+ * Plan: the list of work items (block of query tokens x kv head), heaviest first.
+ * Host-only.  It also owns the pinned staging through which the kernel reads that
+ * list (OSERVE_PLAN_RING slots, same reuse rule as the decode plan).
+ *
+ *   context_lens_host  [batch] int32 host, L_b in [1, max_pages_per_seq * page_size]
+ *   q_lens_host        [batch] int32 host, n_b in [1, L_b]
+ *   device_id          HIP device the plan will be launched on; -1 = planning only
+ *   capacity           largest batch a later update may bring (>= batch)
+ *   max_query_tokens   largest sum of n_b a later update may bring
+ *
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_CONTEXT_LEN (a length out of
+ * range or n_b > L_b), OSERVE_ERR_PLAN_MISMATCH (more query tokens than max_query_tokens),
+ * OSERVE_ERR_DEVICE.  On error *plan_out is null.
+ */
+oserve_status_t oserve_prefill_plan_create(const int32_t* context_lens_host, const int32_t* q_lens_host,
+                                           int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
+                                           int32_t head_dim, int32_t page_size, int32_t max_pages_per_seq,
+                                           int32_t device_id, int32_t capacity, int64_t max_query_tokens,
+                                           oserve_prefill_plan_t** plan_out);
+/* Re-plan in place; no allocation.  On error the plan keeps its previous contents. */
+oserve_status_t oserve_prefill_plan_update(oserve_prefill_plan_t* plan, const int32_t* context_lens_host,
+                                           const int32_t* q_lens_host, int32_t batch);
+void oserve_prefill_plan_destroy(oserve_prefill_plan_t* plan); /* null allowed; launches must have completed */
+int32_t oserve_prefill_plan_num_work_items(const oserve_prefill_plan_t* plan);
+int64_t oserve_prefill_plan_query_tokens(const oserve_prefill_plan_t* plan);  /* sum of n_b */
+int32_t oserve_prefill_plan_block_tokens(const oserve_prefill_plan_t* plan);  /* query tokens per work item */
+/* Item i of the launch order: fields = {request, kv_head, q_begin, q_row0, context_len, q_len}. */
+oserve_status_t oserve_prefill_plan_item(const oserve_prefill_plan_t* plan, int32_t i, int32_t fields[6]);
+
+/*
+ * Enqueues the prefill kernel on `stream` and returns without waiting (except for
+ * the staging-slot reuse described above).  All pointers are device pointers:
+ *   q            bf16 [sum n_b, num_q_heads, head_dim], contiguous, 16-byte aligned
+ *   k_pages,
+ *   v_pages      as for oserve_paged_decode_attn; slots at or beyond L_b may hold anything
+ *   block_table  int32 [batch, max_pages_per_seq]
+ *   scale        multiplies the fp32 score
+ *   out          fp32 [sum n_b, num_q_heads, head_dim], contiguous
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (alignment), OSERVE_ERR_PLAN_MISMATCH
+ * (plan without device), OSERVE_ERR_DEVICE.  Block-table entries outside the pool: undefined.
+ */
+oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const void* q, const void* k_pages,
+                                          const void* v_pages, const int32_t* block_table, float scale,
+                                          float* out, void* stream);
+/* Optional timing of the kernel, as oserve_plan_enable_timing / oserve_plan_split_kernel_ms. */
+oserve_status_t oserve_prefill_plan_enable_timing(oserve_prefill_plan_t* plan, int32_t enable);
+oserve_status_t oserve_prefill_plan_kernel_ms(oserve_prefill_plan_t* plan, float* mean_ms, int32_t* count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,26 @@ def _load() -> ctypes.CDLL:
     lib.oserve_plan_enable_timing.argtypes = [vp, i32]
     lib.oserve_plan_split_kernel_ms.restype = ctypes.c_int
     lib.oserve_plan_split_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
+    i64 = ctypes.c_int64
+    lib.oserve_prefill_plan_create.restype = ctypes.c_int
+    lib.oserve_prefill_plan_create.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.POINTER(vp)]
+    lib.oserve_prefill_plan_update.restype = ctypes.c_int
+    lib.oserve_prefill_plan_update.argtypes = [vp, vp, vp, i32]
+    lib.oserve_prefill_plan_destroy.restype = None
+    lib.oserve_prefill_plan_destroy.argtypes = [vp]
+    for name in ("oserve_prefill_plan_num_work_items", "oserve_prefill_plan_block_tokens"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp]
+    lib.oserve_prefill_plan_query_tokens.restype = i64
+    lib.oserve_prefill_plan_query_tokens.argtypes = [vp]
+    lib.oserve_prefill_plan_item.restype = ctypes.c_int
+    lib.oserve_prefill_plan_item.argtypes = [vp, i32, pi32]
+    lib.oserve_paged_prefill_attn.restype = ctypes.c_int
+    lib.oserve_paged_prefill_attn.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_prefill_plan_enable_timing.restype = ctypes.c_int
+    lib.oserve_prefill_plan_enable_timing.argtypes = [vp, i32]
+    lib.oserve_prefill_plan_kernel_ms.restype = ctypes.c_int
+    lib.oserve_prefill_plan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
     lib.oserve_status_string.restype = ctypes.c_char_p
     lib.oserve_status_string.argtypes = [ctypes.c_int]
     return lib
@@ -206,3 +226,93 @@ class DecodeAttention:
             self.plan.update(inputs.context_lens_host)
         return paged_decode_attn(self.plan, self.workspace, inputs.q, inputs.k_pages, inputs.v_pages,
                                  inputs.block_table, inputs.context_lens, inputs.scale, self.out)
+
+
+class PrefillPlan:
+    """Owns an oserve_prefill_plan_t*.  Mirrors oserve_prefill_plan_* one to one."""
+
+    def __init__(self, context_lens_host, q_lens_host, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                 page_size: int, max_pages_per_seq: int, device_id: int = 0, capacity: int | None = None,
+                 max_query_tokens: int | None = None):
+        lens, qlens = _host_lens(context_lens_host), _host_lens(q_lens_host)
+        if lens.shape != qlens.shape:
+            raise ValueError("context_lens_host and q_lens_host must have the same length")
+        self._h = ctypes.c_void_p()
+        st = lib.oserve_prefill_plan_create(lens.ctypes.data, qlens.ctypes.data, len(lens), num_q_heads, num_kv_heads,
+                                            head_dim, page_size, max_pages_per_seq, device_id,
+                                            len(lens) if capacity is None else capacity,
+                                            int(qlens.sum()) if max_query_tokens is None else max_query_tokens,
+                                            ctypes.byref(self._h))
+        if st != OK:
+            raise OserveError(st, "oserve_prefill_plan_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def update(self, context_lens_host, q_lens_host) -> None:
+        lens, qlens = _host_lens(context_lens_host), _host_lens(q_lens_host)
+        st = lib.oserve_prefill_plan_update(self._h, lens.ctypes.data, qlens.ctypes.data, len(lens))
+        if st != OK:
+            raise OserveError(st, "oserve_prefill_plan_update")
+
+    @property
+    def num_work_items(self) -> int:
+        return lib.oserve_prefill_plan_num_work_items(self._h)
+
+    @property
+    def query_tokens(self) -> int:
+        return lib.oserve_prefill_plan_query_tokens(self._h)
+
+    @property
+    def block_tokens(self) -> int:
+        return lib.oserve_prefill_plan_block_tokens(self._h)
+
+    def item(self, i: int) -> dict:
+        f = (ctypes.c_int32 * 6)()
+        st = lib.oserve_prefill_plan_item(self._h, i, f)
+        if st != OK:
+            raise OserveError(st, "oserve_prefill_plan_item")
+        return dict(zip(("request", "kv_head", "q_begin", "q_row0", "context_len", "q_len"), list(f)))
+
+    def enable_timing(self, enable: bool = True) -> None:
+        st = lib.oserve_prefill_plan_enable_timing(self._h, int(enable))
+        if st != OK:
+            raise OserveError(st, "oserve_prefill_plan_enable_timing")
+
+    def kernel_ms(self):
+        ms, n = ctypes.c_float(), ctypes.c_int32()
+        st = lib.oserve_prefill_plan_kernel_ms(self._h, ctypes.byref(ms), ctypes.byref(n))
+        if st != OK:
+            raise OserveError(st, "oserve_prefill_plan_kernel_ms")
+        return ms.value, n.value
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) and self._h.value and lib is not None:
+            lib.oserve_prefill_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = destroy
+
+
+def paged_prefill_attn(plan: PrefillPlan, q: torch.Tensor, k_pages: torch.Tensor, v_pages: torch.Tensor,
+                       block_table: torch.Tensor, scale: float, out: torch.Tensor,
+                       stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_prefill_attn on torch tensors (layout checks only; no arithmetic here)."""
+    if not (q.is_cuda and k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda and out.is_cuda):
+        raise ValueError("all tensors must be device tensors")
+    if q.dtype != torch.bfloat16 or k_pages.dtype != torch.bfloat16 or v_pages.dtype != torch.bfloat16:
+        raise TypeError("q / k_pages / v_pages must be bf16")
+    if block_table.dtype != torch.int32 or out.dtype != torch.float32:
+        raise TypeError("block_table must be int32 and out fp32")
+    for t in (q, k_pages, v_pages, block_table, out):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    if k_pages.shape != v_pages.shape or out.shape != q.shape or q.shape[0] != plan.query_tokens:
+        raise ValueError("shape mismatch")
+    s = torch.cuda.current_stream(q.device) if stream is None else stream
+    st = lib.oserve_paged_prefill_attn(plan.handle, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                       ctypes.c_float(scale), _ptr(out), ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_paged_prefill_attn")
+    return out

@@ -51,4 +51,31 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
                         hipEvent_t start, hipEvent_t stop);
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
+// ---- chunked prefill (prefill.hip) ----
+// One workgroup's work: a block of query tokens of one request against one kv head.
+struct PrefillItem {
+    int32_t request;       // index into block_table rows
+    int32_t kv_head;
+    int32_t q_begin;       // first query token of the block, counted within the request
+    int32_t q_row0;        // packed row (in q / out) of the request's query token 0
+    int32_t context_len;   // L: cached tokens of the request, the new ones included
+    int32_t q_len;         // n: new query tokens of the request
+    int32_t pad[2];
+};
+static_assert(sizeof(PrefillItem) == 32, "item layout is part of the kernel interface");
+
+struct PrefillParams {
+    const PrefillItem* items;      // pinned host memory as the device addresses it, launch order
+    const uint16_t* q;             // bf16 bits [sum n, Hq, D], requests packed
+    const uint16_t* k_pages;       // bf16 bits [P, Hkv, page_size, D]
+    const uint16_t* v_pages;
+    const int32_t* block_table;    // [B, max_pages_per_seq]
+    float* out;                    // [sum n, Hq, D]
+    float scale_log2e;
+    int32_t num_q_heads, num_kv_heads, group, group_shift, max_pages_per_seq, tile_shift;
+};
+
+hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
+                          hipEvent_t start, hipEvent_t stop);
+
 }  // namespace oserve

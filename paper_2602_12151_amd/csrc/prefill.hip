@@ -1,0 +1,277 @@
+// gfx950 kernel: causal chunked-prefill attention over the paged KV cache.
+//
+// What is computed: the prefill side of paper section 2 ("Phases of LLM inference": the prompt's
+// tokens are processed in parallel, compute-bound), in the form a serving engine runs it next to
+// decode steps: request b brings n_b new query tokens whose keys/values are already the last n_b
+// of its L_b cached tokens; query token i sits at position p = L_b - n_b + i and attends to the
+// cached tokens 0..p.  n_b = 1 is a decode step.
+//
+// How, on CDNA4: one workgroup of four wavefronts per (request, kv head, block of query tokens).
+// Every wavefront owns 64 score columns = (64 / G) query tokens x the G heads of the GQA group, so
+// the workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
+//   * the four wavefronts copy the 32-key K and V tiles (16 KB) from the page pool into LDS with
+//     coalesced 16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free),
+//     double-buffered, one barrier per step; the loads of step s+1 are in flight during step s;
+//   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
+//     registers as the B operand for the whole item);
+//   * online softmax in the log2 domain, per-column state lane-local, maxima exchanged across
+//     lanes only when some lane's keys beat the running maximum; the causal mask is a select and
+//     is applied only on the steps that straddle a wavefront's diagonal;
+//   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
+//     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
+//     and V^T is assembled to match with byte permutes.
+// Accumulation is fp32; P is rounded to bf16 for the second product.
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
+#include <cstdint>
+#include <type_traits>
+
+#include "kernels.h"
+
+namespace oserve {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+constexpr int kPrefillThreads = 256;
+constexpr int kStepKeys = 32;
+
+template <int D>
+__global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const PrefillParams p) {
+    static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
+    constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
+    constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
+    constexpr int ROW = D * 2 + 16;      // bytes of one key's row in LDS (padded)
+    constexpr int TILE = kStepKeys * ROW;
+    constexpr int CT = 4;                // 16-column tiles per wavefront
+    __shared__ __align__(16) unsigned char lds[2][2][TILE];   // [buffer][K, V]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i16 = lane & 15;
+    const int g4 = lane >> 4;
+
+    // ---- the item: read by every lane from pinned host memory, then made wave-uniform ----
+    const PrefillItem* ip = p.items + blockIdx.x;
+    const int b = __builtin_amdgcn_readfirstlane(ip->request);
+    const int kvh = __builtin_amdgcn_readfirstlane(ip->kv_head);
+    const int q_begin = __builtin_amdgcn_readfirstlane(ip->q_begin);
+    const int q_row0 = __builtin_amdgcn_readfirstlane(ip->q_row0);   // packed row of the request's query 0
+    const int L = __builtin_amdgcn_readfirstlane(ip->context_len);
+    const int n = __builtin_amdgcn_readfirstlane(ip->q_len);
+
+    const int gshift = p.group_shift;
+    const int rt = 64 >> gshift;                      // query tokens per wavefront
+    const int tok0 = q_begin + wave * rt;             // this wavefront's first query token
+    const int first_pos = L - n;                      // position of the request's query 0
+    // columns c = 16*ct + i16  ->  token tok0 + (c >> gshift), head c & (G-1); tokens past the
+    // request's last one are computed as copies of it and not stored
+    int tok[CT], pos[CT];
+    bf16x8 qf[CT][KK];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int c = 16 * ct + i16;
+        tok[ct] = tok0 + (c >> gshift);
+        const int t_eff = min(tok[ct], n - 1);
+        pos[ct] = first_pos + t_eff;
+        const int head = kvh * p.group + (c & (p.group - 1));
+        const uint16_t* qrow = p.q + (static_cast<int64_t>(q_row0 + t_eff) * p.num_q_heads + head) * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            qf[ct][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow + (4 * kk + g4) * 8));
+    }
+    const int pos_min = first_pos + min(tok0, n - 1);             // wave-uniform
+    const int pos_max = first_pos + min(tok0 + rt - 1, n - 1);
+    const int blk_last = min(q_begin + 4 * rt, n) - 1;            // last query token of the block
+    const int num_steps = (first_pos + blk_last) / kStepKeys + 1; // keys 0..pos of that token
+
+    // ---- where the 16-token tiles live (same walk as the decode kernel) ----
+    const int32_t* bt_row = p.block_table + static_cast<int64_t>(b) * p.max_pages_per_seq;
+    const int last_tile = (L - 1) >> 4;
+    const int tile_mask = (1 << p.tile_shift) - 1;
+    const int64_t page_elems = (static_cast<int64_t>(p.num_kv_heads) * 16 * D) << p.tile_shift;
+    const int64_t head_off = (static_cast<int64_t>(kvh) * 16 * D) << p.tile_shift;
+    auto tile_base_of = [&](int u) -> int64_t {   // clamped: never reads a table entry the request does not own
+        const int t = min(u, last_tile);
+        const int pid = __builtin_amdgcn_readfirstlane(bt_row[t >> p.tile_shift]);
+        return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (16 * D);
+    };
+
+    // ---- staging: thread t copies bytes [16t, 16t+16) of each 4 KB tile (K and V, two tiles per step) ----
+    uint4 stage[4];
+    const int st_key = tid >> 4;     // key within the 16-key tile
+    const int st_col = tid & 15;     // 16-byte chunk within the key's row
+    auto prefetch = [&](int step) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int64_t base = tile_base_of(2 * step + h) + tid * 8;
+            stage[h] = *reinterpret_cast<const uint4*>(p.k_pages + base);
+            stage[2 + h] = *reinterpret_cast<const uint4*>(p.v_pages + base);
+        }
+    };
+    auto commit = [&](int step, int buf) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // keys at or beyond the context may hold anything: zero them (a NaN there would
+            // survive a zero probability in the value product)
+            const bool live = kStepKeys * step + 16 * h + st_key < L;
+            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+            const int off = (16 * h + st_key) * ROW + st_col * 16;
+            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[h] : z;
+            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[2 + h] : z;
+        }
+    };
+
+    f32x4 acc[EV][CT];
+#pragma unroll
+    for (int e = 0; e < EV; ++e)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[e][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m[CT], l[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) { m[ct] = -INFINITY; l[ct] = 0.f; }
+
+    auto compute = [&](int step, int buf, auto masked) {
+        const unsigned char* kt = lds[buf][0];
+        const unsigned char* vt = lds[buf][1];
+        // scores of both 16-key halves against the 64 columns
+        f32x4 s[CT][2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            bf16x8 kf[KK];
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+                kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + (16 * h + i16) * ROW + (4 * kk + g4) * 16));
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[ct][kk], a, 0, 0, 0);
+                s[ct][h] = a;
+            }
+        }
+        // online softmax per column tile; lane (i16, g4) holds keys 4*g4+r of each half for column i16
+        bf16x8 pb[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            float x[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = s[ct][h][r] * p.scale_log2e;
+                    if constexpr (decltype(masked)::value) {
+                        const int key = kStepKeys * step + 16 * h + 4 * g4 + r;
+                        v = key <= pos[ct] ? v : -INFINITY;
+                    }
+                    x[4 * h + r] = v;
+                }
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            if (__builtin_amdgcn_ballot_w64(mx > m[ct]) != 0) {
+                mx = fmaxf(mx, xor_f32(mx, 16));
+                mx = fmaxf(mx, xor_f32(mx, 32));
+                const float m_new = fmaxf(m[ct], mx);
+                const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_new);
+                l[ct] *= alpha;
+#pragma unroll
+                for (int e = 0; e < EV; ++e) acc[e][ct] *= alpha;
+                m[ct] = m_new;
+            }
+            float sum = 0.f;
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f32x2 pp;
+                pp[0] = __builtin_amdgcn_exp2f(x[2 * j] - m[ct]);
+                pp[1] = __builtin_amdgcn_exp2f(x[2 * j + 1] - m[ct]);
+                sum += pp[0] + pp[1];
+                w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+            }
+            l[ct] += sum;
+            pb[ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+        }
+        // value product: contraction index 8*g4 + j  <->  key 16*(j/4) + 4*g4 + j%4
+        uint32_t vw[8][4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint4 r = *reinterpret_cast<const uint4*>(vt + (16 * (j >> 2) + 4 * g4 + (j & 3)) * ROW + i16 * 16);
+            vw[j][0] = r.x; vw[j][1] = r.y; vw[j][2] = r.z; vw[j][3] = r.w;
+        }
+#pragma unroll
+        for (int e = 0; e < EV; ++e) {
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+            uint32_t a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                a[j] = __builtin_amdgcn_perm(vw[2 * j + 1][e >> 1], vw[2 * j][e >> 1], sel);
+            }
+            const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(a[0], a[1], a[2], a[3]));
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[ct], acc[e][ct], 0, 0, 0);
+        }
+    };
+    using Plain = std::integral_constant<bool, false>;
+    using Masked = std::integral_constant<bool, true>;
+
+    // ---- main loop: one barrier per 32-key step ----
+    prefetch(0);
+    commit(0, 0);
+    __syncthreads();
+    for (int step = 0; step < num_steps; ++step) {
+        const int buf = step & 1;
+        const bool more = step + 1 < num_steps;
+        if (more) prefetch(step + 1);
+        const int first_key = kStepKeys * step;
+        if (first_key <= pos_max) {                       // otherwise every key is in this wavefront's future
+            if (first_key + kStepKeys - 1 > pos_min) compute(step, buf, Masked{});
+            else compute(step, buf, Plain{});
+        }
+        if (more) commit(step + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- write out: lane holds column i16 of each tile, dims 8*(4*g4 + r) + e ----
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        float l_tot = l[ct] + xor_f32(l[ct], 16);
+        l_tot += xor_f32(l_tot, 32);
+        const int c = 16 * ct + i16;
+        if (tok[ct] < n) {
+            const int head = kvh * p.group + (c & (p.group - 1));
+            float* dst = p.out + (static_cast<int64_t>(q_row0 + tok[ct]) * p.num_q_heads + head) * D + 4 * EV * g4;
+            const float inv = 1.f / l_tot;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int e4 = 0; e4 < EV / 4; ++e4) {
+                    float4 o;
+                    o.x = acc[4 * e4 + 0][ct][r] * inv;
+                    o.y = acc[4 * e4 + 1][ct][r] * inv;
+                    o.z = acc[4 * e4 + 2][ct][r] * inv;
+                    o.w = acc[4 * e4 + 3][ct][r] * inv;
+                    *reinterpret_cast<float4*>(dst + r * EV + 4 * e4) = o;
+                }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
+                          hipEvent_t start, hipEvent_t stop) {
+    if (num_items <= 0) return hipSuccess;
+    if (head_dim != 128) return hipErrorInvalidValue;
+    hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(kPrefillThreads), 0, stream,
+                          start, stop, 0, p);
+    return hipGetLastError();
+}
+
+}  // namespace oserve

@@ -1,0 +1,115 @@
+"""GPU-vs-oracle parity of the chunked-prefill path, called through the C ABI.
+
+Same bar as the decode path: max-abs error <= 1e-2 and relative L2 error <= 2e-3
+against the fp64 oracle on the same seeded bits.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import paged_attention_oracle as oracle
+from paper_2602_12151_amd import binding, workloads as wl
+from tests import gpu_helpers as gh
+
+pytestmark = pytest.mark.gpu
+
+
+def make_case(lens, qlens, hq=32, hkv=8, page_size=16, seed=0, poison=False):
+    lens = np.asarray(lens, dtype=np.int32)
+    qlens = np.asarray(qlens, dtype=np.int32)
+    w = wl.Workload(9, "prefill", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=128, page_size=page_size)
+    cpu = wl.make_inputs(w, device="cpu", seed=seed, lens=lens)
+    g = torch.Generator().manual_seed(seed + 12345)
+    q = torch.randn(int(qlens.sum()), hq, 128, generator=g).to(torch.bfloat16)
+    if poison:   # NaN in every slot past a request's context, and in every page no request owns
+        used = np.zeros(cpu.k_pages.shape[0], dtype=bool)
+        used[cpu.used_pages] = True
+        cpu.k_pages[~torch.from_numpy(used)] = float("nan")
+        cpu.v_pages[~torch.from_numpy(used)] = float("nan")
+        bt = cpu.block_table.numpy()
+        for b, L in enumerate(lens):
+            if L % page_size:
+                last = int(bt[b, (L - 1) // page_size])
+                cpu.k_pages[last, :, L % page_size:, :] = float("nan")
+                cpu.v_pages[last, :, L % page_size:, :] = float("nan")
+    return w, cpu, q, lens, qlens
+
+
+def run_gpu(w, cpu, q, lens, qlens):
+    plan = binding.PrefillPlan(lens, qlens, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
+                               cpu.block_table.shape[1], 0)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    binding.paged_prefill_attn(plan, q.cuda(), cpu.k_pages.cuda(), cpu.v_pages.cuda(), cpu.block_table.cuda(),
+                               w.scale, out)
+    torch.cuda.synchronize()
+    return out, plan
+
+
+def reference(w, cpu, q, lens, qlens):
+    return oracle.paged_prefill_attn(q, cpu.k_pages, cpu.v_pages, cpu.block_table.numpy(), lens, qlens, w.scale)
+
+
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (4, 2), (16, 1)])
+def test_mixed_chunks_all_group_sizes(hq, hkv):
+    """Whole prompts, chunks at the end of longer contexts, single decode tokens, ragged last blocks."""
+    lens = [1, 17, 300, 300, 1000, 64, 65, 2049, 513]
+    qlens = [1, 17, 300, 37, 64, 64, 1, 100, 257]
+    case = make_case(lens, qlens, hq, hkv, seed=hq + hkv, poison=True)
+    out, plan = run_gpu(*case)
+    assert plan.query_tokens == sum(qlens)
+    print(f"hq={hq} hkv={hkv}:", gh.assert_parity(out, reference(*case), f"prefill hq={hq} hkv={hkv}"),
+          "items", plan.num_work_items, "block", plan.block_tokens)
+
+
+@pytest.mark.parametrize("page_size", [32, 64])
+def test_larger_pages(page_size):
+    lens = [33, 700, 129, 4000]
+    qlens = [33, 128, 2, 500]
+    case = make_case(lens, qlens, 32, 8, page_size=page_size, seed=page_size, poison=True)
+    out, _ = run_gpu(*case)
+    gh.assert_parity(out, reference(*case), f"prefill page={page_size}")
+
+
+def test_one_token_per_request_matches_the_decode_path_and_oracle():
+    lens = [5, 300, 77, 1024, 4097]
+    case = make_case(lens, [1] * len(lens), 32, 8, seed=3)
+    w, cpu, q, lens_a, qlens = case
+    out, _ = run_gpu(*case)
+    ref = reference(*case)
+    gh.assert_parity(out, ref, "prefill n=1")
+
+
+def test_whole_prompt_long():
+    """One whole prompt of 3000 tokens (n = L): every block is on the diagonal at its end."""
+    case = make_case([3000], [3000], 8, 2, seed=5)
+    out, plan = run_gpu(*case)
+    print("whole prompt:", gh.assert_parity(out, reference(*case), "whole prompt"), "items", plan.num_work_items)
+
+
+def test_update_and_rerun_is_bit_identical():
+    case = make_case([700, 90], [200, 90], 32, 8, seed=9)
+    w, cpu, q, lens, qlens = case
+    out1, plan = run_gpu(*case)
+    out2 = torch.empty_like(out1)
+    for _ in range(2 * binding.PLAN_RING + 1):     # wraps the staging ring
+        plan.update(lens, qlens)
+        binding.paged_prefill_attn(plan, q.cuda(), cpu.k_pages.cuda(), cpu.v_pages.cuda(), cpu.block_table.cuda(),
+                                   w.scale, out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2)
+
+
+def test_plan_errors():
+    with pytest.raises(binding.OserveError) as e:
+        binding.PrefillPlan([10], [11], 32, 8, 128, 16, 4, 0)          # n > L
+    assert e.value.status == binding.ERR_CONTEXT_LEN
+    with pytest.raises(binding.OserveError) as e:
+        binding.PrefillPlan([10], [4], 24, 8, 128, 16, 4, 0)           # group 3
+    assert e.value.status == binding.ERR_SHAPE
+    with pytest.raises(binding.OserveError) as e:
+        binding.PrefillPlan([10], [4], 32, 8, 64, 16, 4, 0)            # head_dim 64
+    assert e.value.status == binding.ERR_SHAPE
+    plan = binding.PrefillPlan([100], [10], 32, 8, 128, 16, 8, 0, max_query_tokens=16)
+    with pytest.raises(binding.OserveError) as e:
+        plan.update([100], [17])
+    assert e.value.status == binding.ERR_PLAN_MISMATCH

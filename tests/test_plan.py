@@ -158,3 +158,28 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(binding.lib, n), n
     assert binding.status_string(0) == "ok"
+
+
+def test_prefill_plan_items_cover_every_query_block_once():
+    lens = [1, 17, 300, 1000, 2049]
+    qlens = [1, 17, 37, 1000, 100]
+    for hq, hkv in [(32, 8), (16, 1), (8, 8)]:
+        plan = binding.PrefillPlan(lens, qlens, hq, hkv, 128, 16, 129, -1)
+        qb = plan.block_tokens
+        assert qb == 256 // (hq // hkv)
+        seen = set()
+        prev = None
+        rows = np.concatenate([[0], np.cumsum(qlens)])
+        for i in range(plan.num_work_items):
+            it = plan.item(i)
+            b = it["request"]
+            assert it["context_len"] == lens[b] and it["q_len"] == qlens[b] and it["q_row0"] == rows[b]
+            assert it["q_begin"] % qb == 0 and it["q_begin"] < qlens[b]
+            key = (b, it["kv_head"], it["q_begin"])
+            assert key not in seen
+            seen.add(key)
+            work = lens[b] - qlens[b] + min(it["q_begin"] + qb, qlens[b])
+            assert prev is None or work <= prev          # heaviest first
+            prev = work
+        assert len(seen) == sum(-(-n // qb) for n in qlens) * hkv
+        assert plan.query_tokens == sum(qlens)
