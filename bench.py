@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--copy-probe", type=int, default=0, metavar="BYTES",
                     help="instead of the benchmark, run a plain device copy of BYTES bytes --steps times "
                          "(the known-size kernel that hardware byte counters are scaled by)")
+    ap.add_argument("--prefill", type=int, default=-1, metavar="W",
+                    help="instead of the decode benchmark, time the chunked-prefill kernel on prefill workload W "
+                         "(0: 16 whole prompts of 4096 tokens; 1: 8 chunks of 2048 tokens at the end of 32768-token "
+                         "contexts; 2: 64 chunks of 512 tokens on the heterogeneous mix's long requests), Llama-3-8B heads")
     ap.add_argument("--cpu-token-heads", type=float, default=120e6,
                     help="size of the oracle's sample in (token, query head) pairs")
     return ap.parse_args()
@@ -93,6 +97,71 @@ def cpu_baseline(inp, wl, torch, budget_token_heads):
     }
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 peak
+
+PREFILL_WORKLOADS = {
+    0: ("16 whole prompts of 4096 tokens", lambda: (np.full(16, 4096), np.full(16, 4096))),
+    1: ("8 chunks of 2048 tokens ending 32768-token contexts", lambda: (np.full(8, 32768), np.full(8, 2048))),
+    2: ("64 chunks of 512 tokens ending contexts uniform in [8192, 32768]", None),
+}
+
+
+def bench_prefill(args, torch, binding, wl):
+    """One step = oserve_prefill_plan_update + the prefill kernel on inputs resident in HBM."""
+    name, make = PREFILL_WORKLOADS[args.prefill]
+    if make is None:
+        lens = wl.CounterRng(20260212 + 100 + args.prefill).integers(8192, 32768, 64)
+        qlens = np.full(64, 512)
+    else:
+        lens, qlens = make()
+    lens, qlens = lens.astype(np.int32), qlens.astype(np.int32)
+    w = wl.Workload(100 + args.prefill, "prefill", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 1)
+    q = torch.randn(int(qlens.sum()), w.num_q_heads, w.head_dim, generator=gen, device="cuda").to(torch.bfloat16)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    plan = binding.PrefillPlan(lens, qlens, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
+                               inp.block_table.shape[1], 0)
+
+    def step():
+        plan.update(lens, qlens)
+        binding.paged_prefill_attn(plan, q, inp.k_pages, inp.v_pages, inp.block_table, w.scale, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    plan.enable_timing(True)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = max(wall_ms, start.elapsed_time(stop)) / args.steps
+    kernel_ms, cnt = plan.kernel_ms()
+    plan.enable_timing(False)
+    # 2 products x 2 flop x head_dim per (query token, visible key) and query head; query i of a request sees L - n + i + 1 keys
+    pairs = sum(int(n) * (int(L) - int(n)) + int(n) * (int(n) + 1) // 2 for L, n in zip(lens, qlens))
+    flop = 4.0 * w.head_dim * w.num_q_heads * pairs
+    value = flop / (ms_per_step * 1e-3) / 1e12
+    achieved = flop / (kernel_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "chunked-prefill attention TFLOP/s (causal, paged KV)", "value": round(value, 1), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"prefill{args.prefill}: {name}; 32q/8kv heads, head_dim 128, page 16, "
+                               f"{int(qlens.sum())} query tokens, {flop / 1e12:.3f} TFLOP per step",
+                   "work_items": plan.num_work_items, "block_tokens": plan.block_tokens},
+        "roofline": {"bound": "mfma", "kernel": "paged_prefill_kernel", "achieved": round(achieved, 1),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None, "avg_kernel_ms": round(kernel_ms, 5), "launches_timed": cnt,
+                     "algorithmic_flop_per_launch": flop},
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -113,6 +182,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes": args.copy_probe, "launches": args.steps}))
+        return
+    if args.prefill >= 0:
+        bench_prefill(args, torch, binding, wl)
         return
     w = wl.WORKLOADS[args.config]
     sets, nbytes = build_inputs(w, wl, torch)

@@ -190,7 +190,7 @@ const char* oserve_status_string(oserve_status_t status);
  * its decode requests through oserve_paged_decode_attn and its prefill chunks
  * through this call on the same stream.
  *
- * One workgroup of four wavefronts handles a block of 256 / G query tokens of one
+ * One workgroup of eight wavefronts handles a block of 256 / G query tokens of one
  * request against one kv head (G = num_q_heads / num_kv_heads); K and V tiles go
  * through LDS; both products run on bf16 MFMA with fp32 accumulation; the
  * probabilities are rounded to bf16 for the second product.
@@ -235,9 +235,9 @@ oserve_status_t oserve_prefill_plan_item(const oserve_prefill_plan_t* plan, int3
  *   k_pages,
  *   v_pages      as for oserve_paged_decode_attn; slots at or beyond L_b may hold anything
  *   block_table  int32 [batch, max_pages_per_seq]
- *   scale        multiplies the fp32 score
+ *   scale        multiplies the fp32 score; must be positive and finite
  *   out          fp32 [sum n_b, num_q_heads, head_dim], contiguous
- * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (alignment), OSERVE_ERR_PLAN_MISMATCH
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (alignment, scale), OSERVE_ERR_PLAN_MISMATCH
  * (plan without device), OSERVE_ERR_DEVICE.  Block-table entries outside the pool: undefined.
  */
 oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const void* q, const void* k_pages,

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -201,6 +202,7 @@ oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const voi
                                           float* out, void* stream_v) {
     if (!plan || !q || !k_pages || !v_pages || !block_table || !out) return OSERVE_ERR_NULL;
     if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
+    if (!(scale > 0.f) || !std::isfinite(scale)) return OSERVE_ERR_SHAPE;   // the kernel orders raw scores
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pages) |
          reinterpret_cast<uintptr_t>(v_pages) | reinterpret_cast<uintptr_t>(out)) & 15u)
         return OSERVE_ERR_SHAPE;

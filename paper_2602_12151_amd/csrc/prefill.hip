@@ -6,10 +6,11 @@
 // of its L_b cached tokens; query token i sits at position p = L_b - n_b + i and attends to the
 // cached tokens 0..p.  n_b = 1 is a decode step.
 //
-// How, on CDNA4: one workgroup of four wavefronts per (request, kv head, block of query tokens).
-// Every wavefront owns 64 score columns = (64 / G) query tokens x the G heads of the GQA group, so
-// the workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
-//   * the four wavefronts copy the 32-key K and V tiles (16 KB) from the page pool into LDS with
+// How, on CDNA4: one workgroup of eight wavefronts (two per SIMD, so that one wavefront's MFMAs
+// overlap the other's softmax arithmetic) per (request, kv head, block of query tokens).  Every
+// wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
+// workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
+//   * the wavefronts copy the 32-key K and V tiles (16 KB) from the page pool into LDS with
 //     coalesced 16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free),
 //     double-buffered, one barrier per step; the loads of step s+1 are in flight during step s;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
@@ -39,7 +40,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-constexpr int kPrefillThreads = 256;
+constexpr int kPrefillWaves = 8;
+constexpr int kPrefillThreads = 64 * kPrefillWaves;
+constexpr int kColTiles = 2;        // 16-column tiles per wavefront
 constexpr int kStepKeys = 32;
 
 template <int D>
@@ -49,7 +52,7 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
     constexpr int ROW = D * 2 + 16;      // bytes of one key's row in LDS (padded)
     constexpr int TILE = kStepKeys * ROW;
-    constexpr int CT = 4;                // 16-column tiles per wavefront
+    constexpr int CT = kColTiles;
     __shared__ __align__(16) unsigned char lds[2][2][TILE];   // [buffer][K, V]
 
     const int tid = threadIdx.x;
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
     const int n = __builtin_amdgcn_readfirstlane(ip->q_len);
 
     const int gshift = p.group_shift;
-    const int rt = 64 >> gshift;                      // query tokens per wavefront
+    const int rt = (16 * CT) >> gshift;               // query tokens per wavefront
     const int tok0 = q_begin + wave * rt;             // this wavefront's first query token
     const int first_pos = L - n;                      // position of the request's query 0
     // columns c = 16*ct + i16  ->  token tok0 + (c >> gshift), head c & (G-1); tokens past the
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
     }
     const int pos_min = first_pos + min(tok0, n - 1);             // wave-uniform
     const int pos_max = first_pos + min(tok0 + rt - 1, n - 1);
-    const int blk_last = min(q_begin + 4 * rt, n) - 1;            // last query token of the block
+    const int blk_last = min(q_begin + kPrefillWaves * rt, n) - 1;   // last query token of the block
     const int num_steps = (first_pos + blk_last) / kStepKeys + 1; // keys 0..pos of that token
 
     // ---- where the 16-token tiles live (same walk as the decode kernel) ----
@@ -104,29 +107,25 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
         return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (16 * D);
     };
 
-    // ---- staging: thread t copies bytes [16t, 16t+16) of each 4 KB tile (K and V, two tiles per step) ----
-    uint4 stage[4];
-    const int st_key = tid >> 4;     // key within the 16-key tile
-    const int st_col = tid & 15;     // 16-byte chunk within the key's row
+    // ---- staging: per step the workgroup copies two 4 KB K tiles and two 4 KB V tiles; thread t
+    // copies bytes [16 t', 16 t' + 16), t' = t % 256, of tile half t / 256 ----
+    uint4 stage[2];
+    const int st_half = tid >> 8;
+    const int st_key = (tid & 255) >> 4;   // key within the 16-key tile
+    const int st_col = tid & 15;           // 16-byte chunk within the key's row
     auto prefetch = [&](int step) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int64_t base = tile_base_of(2 * step + h) + tid * 8;
-            stage[h] = *reinterpret_cast<const uint4*>(p.k_pages + base);
-            stage[2 + h] = *reinterpret_cast<const uint4*>(p.v_pages + base);
-        }
+        const int64_t base = tile_base_of(2 * step + st_half) + (tid & 255) * 8;
+        stage[0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
+        stage[1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
     };
     auto commit = [&](int step, int buf) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            // keys at or beyond the context may hold anything: zero them (a NaN there would
-            // survive a zero probability in the value product)
-            const bool live = kStepKeys * step + 16 * h + st_key < L;
-            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-            const int off = (16 * h + st_key) * ROW + st_col * 16;
-            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[h] : z;
-            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[2 + h] : z;
-        }
+        // keys at or beyond the context may hold anything: zero them (a NaN there would survive a
+        // zero probability in the value product)
+        const bool live = kStepKeys * step + 16 * st_half + st_key < L;
+        const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+        const int off = (16 * st_half + st_key) * ROW + st_col * 16;
+        *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[0] : z;
+        *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[1] : z;
     };
 
     f32x4 acc[EV][CT];
@@ -166,14 +165,15 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float v = s[ct][h][r] * p.scale_log2e;
+                    float v = s[ct][h][r];   // raw score; the scale is applied inside the exponent below
                     if constexpr (decltype(masked)::value) {
                         const int key = kStepKeys * step + 16 * h + 4 * g4 + r;
                         v = key <= pos[ct] ? v : -INFINITY;
                     }
                     x[4 * h + r] = v;
                 }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            // m is kept in scaled (log2) units; scale > 0 is required, so the order of raw scores is the order of scaled ones
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7]))) * p.scale_log2e;
             if (__builtin_amdgcn_ballot_w64(mx > m[ct]) != 0) {
                 mx = fmaxf(mx, xor_f32(mx, 16));
                 mx = fmaxf(mx, xor_f32(mx, 32));
@@ -189,8 +189,8 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 f32x2 pp;
-                pp[0] = __builtin_amdgcn_exp2f(x[2 * j] - m[ct]);
-                pp[1] = __builtin_amdgcn_exp2f(x[2 * j + 1] - m[ct]);
+                pp[0] = __builtin_amdgcn_exp2f(fmaf(x[2 * j], p.scale_log2e, -m[ct]));
+                pp[1] = __builtin_amdgcn_exp2f(fmaf(x[2 * j + 1], p.scale_log2e, -m[ct]));
                 sum += pp[0] + pp[1];
                 w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
             }
