@@ -10,9 +10,11 @@
 // overlap the other's softmax arithmetic) per (request, kv head, block of query tokens).  Every
 // wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
-//   * the wavefronts copy the 32-key K and V tiles (16 KB) from the page pool into LDS with
-//     coalesced 16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free),
-//     double-buffered, one barrier per step; the loads of step s+1 are in flight during step s;
+//   * the wavefronts copy K and V tiles of kMacroKeys keys from the page pool into LDS with coalesced
+//     16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free),
+//     double-buffered, one barrier per kMacroKeys keys: between two barriers the wavefronts drift
+//     apart, so that one's MFMAs overlap another's softmax arithmetic; the loads of the next
+//     macro step are in flight during the current one;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
 //   * online softmax in the log2 domain, per-column state lane-local, maxima exchanged across
@@ -44,14 +46,16 @@ constexpr int kPrefillWaves = 8;
 constexpr int kPrefillThreads = 64 * kPrefillWaves;
 constexpr int kColTiles = 2;        // 16-column tiles per wavefront
 constexpr int kStepKeys = 32;
+constexpr int kMacroKeys = 128;     // keys staged in LDS per barrier
 
 template <int D>
-__global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void paged_prefill_kernel(const PrefillParams p) {
     static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
     constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
     constexpr int ROW = D * 2 + 16;      // bytes of one key's row in LDS (padded)
-    constexpr int TILE = kStepKeys * ROW;
+    constexpr int TILE = kMacroKeys * ROW;
+    constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
     constexpr int CT = kColTiles;
     __shared__ __align__(16) unsigned char lds[2][2][TILE];   // [buffer][K, V]
 
@@ -107,25 +111,32 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
         return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (16 * D);
     };
 
-    // ---- staging: per step the workgroup copies two 4 KB K tiles and two 4 KB V tiles; thread t
-    // copies bytes [16 t', 16 t' + 16), t' = t % 256, of tile half t / 256 ----
-    uint4 stage[2];
+    // ---- staging: per macro step the workgroup copies kMacroKeys / 16 K tiles and as many V tiles
+    // of 4 KB; thread t copies bytes [16 t', 16 t' + 16), t' = t % 256, of tiles t / 256 + 2 i ----
+    uint4 stage[SUB][2];
     const int st_half = tid >> 8;
     const int st_key = (tid & 255) >> 4;   // key within the 16-key tile
     const int st_col = tid & 15;           // 16-byte chunk within the key's row
-    auto prefetch = [&](int step) {
-        const int64_t base = tile_base_of(2 * step + st_half) + (tid & 255) * 8;
-        stage[0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
-        stage[1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
+    auto prefetch = [&](int macro) {
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            const int64_t base = tile_base_of((kMacroKeys / 16) * macro + 2 * i + st_half) + (tid & 255) * 8;
+            stage[i][0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
+            stage[i][1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
+        }
     };
-    auto commit = [&](int step, int buf) {
-        // keys at or beyond the context may hold anything: zero them (a NaN there would survive a
-        // zero probability in the value product)
-        const bool live = kStepKeys * step + 16 * st_half + st_key < L;
-        const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-        const int off = (16 * st_half + st_key) * ROW + st_col * 16;
-        *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[0] : z;
-        *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[1] : z;
+    auto commit = [&](int macro, int buf) {
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            // keys at or beyond the context may hold anything: zero them (a NaN there would
+            // survive a zero probability in the value product)
+            const int row = 32 * i + 16 * st_half + st_key;
+            const bool live = kMacroKeys * macro + row < L;
+            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+            const int off = row * ROW + st_col * 16;
+            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[i][0] : z;
+            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[i][1] : z;
+        }
     };
 
     f32x4 acc[EV][CT];
@@ -137,9 +148,9 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) { m[ct] = -INFINITY; l[ct] = 0.f; }
 
-    auto compute = [&](int step, int buf, auto masked) {
-        const unsigned char* kt = lds[buf][0];
-        const unsigned char* vt = lds[buf][1];
+    auto compute = [&](int step, int buf, int sub, auto masked) {
+        const unsigned char* kt = lds[buf][0] + sub * (kStepKeys * ROW);
+        const unsigned char* vt = lds[buf][1] + sub * (kStepKeys * ROW);
         // scores of both 16-key halves against the 64 columns
         f32x4 s[CT][2];
 #pragma unroll
@@ -221,20 +232,25 @@ __global__ __launch_bounds__(kPrefillThreads) void paged_prefill_kernel(const Pr
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
 
-    // ---- main loop: one barrier per 32-key step ----
+    // ---- main loop: one barrier per macro step ----
+    const int num_macro = (num_steps + SUB - 1) / SUB;
     prefetch(0);
     commit(0, 0);
     __syncthreads();
-    for (int step = 0; step < num_steps; ++step) {
-        const int buf = step & 1;
-        const bool more = step + 1 < num_steps;
-        if (more) prefetch(step + 1);
-        const int first_key = kStepKeys * step;
-        if (first_key <= pos_max) {                       // otherwise every key is in this wavefront's future
-            if (first_key + kStepKeys - 1 > pos_min) compute(step, buf, Masked{});
-            else compute(step, buf, Plain{});
+    for (int macro = 0; macro < num_macro; ++macro) {
+        const int buf = macro & 1;
+        const bool more = macro + 1 < num_macro;
+        if (more) prefetch(macro + 1);
+#pragma unroll
+        for (int sub = 0; sub < SUB; ++sub) {
+            const int step = macro * SUB + sub;
+            const int first_key = kStepKeys * step;
+            if (first_key <= pos_max) {                   // otherwise every key is in this wavefront's future
+                if (first_key + kStepKeys - 1 > pos_min) compute(step, buf, sub, Masked{});
+                else compute(step, buf, sub, Plain{});
+            }
         }
-        if (more) commit(step + 1, buf ^ 1);
+        if (more) commit(macro + 1, buf ^ 1);
         __syncthreads();
     }
 
