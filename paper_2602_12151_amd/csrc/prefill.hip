@@ -17,9 +17,10 @@
 //     macro step are in flight during the current one;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
-//   * online softmax in the log2 domain, per-column state lane-local, maxima exchanged across
-//     lanes only when some lane's keys beat the running maximum; the causal mask is a select and
-//     is applied only on the steps that straddle a wavefront's diagonal;
+//   * online softmax in the log2 domain, one update per column and macro step, per-column state
+//     lane-local, maxima exchanged across lanes only when some lane's keys beat the running
+//     maximum; the causal mask is a select and is applied only on the macro steps that straddle a
+//     wavefront's diagonal;
 //   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
 //     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
 //     and V^T is assembled to match with byte permutes.
@@ -148,43 +149,49 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) { m[ct] = -INFINITY; l[ct] = 0.f; }
 
-    auto compute = [&](int step, int buf, int sub, auto masked) {
-        const unsigned char* kt = lds[buf][0] + sub * (kStepKeys * ROW);
-        const unsigned char* vt = lds[buf][1] + sub * (kStepKeys * ROW);
-        // scores of both 16-key halves against the 64 columns
-        f32x4 s[CT][2];
+    // One macro step for this wavefront's 16*CT columns, in three phases so that the MFMAs of a
+    // phase are issued back to back: (1) all scores of the kMacroKeys keys, (2) one online-softmax
+    // update per column over all of them, (3) the value products.
+    auto compute = [&](int macro, int buf, auto masked) {
+        const unsigned char* kt = lds[buf][0];
+        const unsigned char* vt = lds[buf][1];
+        f32x4 s[SUB][CT][2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            bf16x8 kf[KK];
+        for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
-                kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kt + (16 * h + i16) * ROW + (4 * kk + g4) * 16));
+            for (int h = 0; h < 2; ++h) {
+                bf16x8 kf[KK];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int kk = 0; kk < KK; ++kk)
+                    kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                        kt + (32 * sub + 16 * h + i16) * ROW + (4 * kk + g4) * 16));
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[ct][kk], a, 0, 0, 0);
-                s[ct][h] = a;
+                for (int ct = 0; ct < CT; ++ct) {
+                    f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[ct][kk], a, 0, 0, 0);
+                    s[sub][ct][h] = a;
+                }
             }
-        }
-        // online softmax per column tile; lane (i16, g4) holds keys 4*g4+r of each half for column i16
-        bf16x8 pb[CT];
+        // lane (i16, g4) holds, for column i16 of each tile, keys 32*sub + 16*h + 4*g4 + r
+        bf16x8 pb[SUB][CT];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
-            float x[8];
+            float mx = -INFINITY;
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float v = s[ct][h][r];   // raw score; the scale is applied inside the exponent below
-                    if constexpr (decltype(masked)::value) {
-                        const int key = kStepKeys * step + 16 * h + 4 * g4 + r;
-                        v = key <= pos[ct] ? v : -INFINITY;
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (decltype(masked)::value) {
+                            const int key = kMacroKeys * macro + 32 * sub + 16 * h + 4 * g4 + r;
+                            s[sub][ct][h][r] = key <= pos[ct] ? s[sub][ct][h][r] : -INFINITY;
+                        }
+                        mx = fmaxf(mx, s[sub][ct][h][r]);
                     }
-                    x[4 * h + r] = v;
-                }
-            // m is kept in scaled (log2) units; scale > 0 is required, so the order of raw scores is the order of scaled ones
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7]))) * p.scale_log2e;
+            // m is kept in scaled (log2) units; the scale is positive, so raw scores order like scaled ones
+            mx *= p.scale_log2e;
             if (__builtin_amdgcn_ballot_w64(mx > m[ct]) != 0) {
                 mx = fmaxf(mx, xor_f32(mx, 16));
                 mx = fmaxf(mx, xor_f32(mx, 32));
@@ -196,37 +203,41 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 m[ct] = m_new;
             }
             float sum = 0.f;
-            uint32_t w[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                f32x2 pp;
-                pp[0] = __builtin_amdgcn_exp2f(fmaf(x[2 * j], p.scale_log2e, -m[ct]));
-                pp[1] = __builtin_amdgcn_exp2f(fmaf(x[2 * j + 1], p.scale_log2e, -m[ct]));
-                sum += pp[0] + pp[1];
-                w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+            for (int sub = 0; sub < SUB; ++sub) {
+                uint32_t w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x2 pp;
+                    pp[0] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1)], p.scale_log2e, -m[ct]));
+                    pp[1] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1) + 1], p.scale_log2e, -m[ct]));
+                    sum += pp[0] + pp[1];
+                    w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+                }
+                pb[sub][ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
             }
             l[ct] += sum;
-            pb[ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
         }
-        // value product: contraction index 8*g4 + j  <->  key 16*(j/4) + 4*g4 + j%4
-        uint32_t vw[8][4];
+        // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint4 r = *reinterpret_cast<const uint4*>(vt + (16 * (j >> 2) + 4 * g4 + (j & 3)) * ROW + i16 * 16);
-            vw[j][0] = r.x; vw[j][1] = r.y; vw[j][2] = r.z; vw[j][3] = r.w;
-        }
+        for (int sub = 0; sub < SUB; ++sub) {
+            uint32_t vw[8][4];
 #pragma unroll
-        for (int e = 0; e < EV; ++e) {
-            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-            uint32_t a[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                a[j] = __builtin_amdgcn_perm(vw[2 * j + 1][e >> 1], vw[2 * j][e >> 1], sel);
+            for (int j = 0; j < 8; ++j) {
+                const uint4 r = *reinterpret_cast<const uint4*>(vt + (32 * sub + 16 * (j >> 2) + 4 * g4 + (j & 3)) * ROW + i16 * 16);
+                vw[j][0] = r.x; vw[j][1] = r.y; vw[j][2] = r.z; vw[j][3] = r.w;
             }
-            const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(a[0], a[1], a[2], a[3]));
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-                acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[ct], acc[e][ct], 0, 0, 0);
+            for (int e = 0; e < EV; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                uint32_t a[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a[j] = __builtin_amdgcn_perm(vw[2 * j + 1][e >> 1], vw[2 * j][e >> 1], sel);
+                const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(a[0], a[1], a[2], a[3]));
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[sub][ct], acc[e][ct], 0, 0, 0);
+            }
         }
     };
     using Plain = std::integral_constant<bool, false>;
@@ -241,14 +252,10 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         const int buf = macro & 1;
         const bool more = macro + 1 < num_macro;
         if (more) prefetch(macro + 1);
-#pragma unroll
-        for (int sub = 0; sub < SUB; ++sub) {
-            const int step = macro * SUB + sub;
-            const int first_key = kStepKeys * step;
-            if (first_key <= pos_max) {                   // otherwise every key is in this wavefront's future
-                if (first_key + kStepKeys - 1 > pos_min) compute(step, buf, sub, Masked{});
-                else compute(step, buf, sub, Plain{});
-            }
+        const int first_key = kMacroKeys * macro;
+        if (first_key <= pos_max) {                       // otherwise every key is in this wavefront's future
+            if (first_key + kMacroKeys - 1 > pos_min) compute(macro, buf, Masked{});
+            else compute(macro, buf, Plain{});
         }
         if (more) commit(macro + 1, buf ^ 1);
         __syncthreads();
