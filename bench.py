@@ -46,6 +46,9 @@ def parse_args():
                     help="instead of the decode benchmark, time the chunked-prefill kernel on prefill workload W "
                          "(0: 16 whole prompts of 4096 tokens; 1: 8 chunks of 2048 tokens at the end of 32768-token "
                          "contexts; 2: 64 chunks of 512 tokens on the heterogeneous mix's long requests), Llama-3-8B heads")
+    ap.add_argument("--migrate", action="store_true",
+                    help="instead of the decode benchmark, time the KV-block migration copies (gather into a staging "
+                         "chunk, scatter into a target pool) of the long requests of the heterogeneous mix")
     ap.add_argument("--cpu-token-heads", type=float, default=120e6,
                     help="size of the oracle's sample in (token, query head) pairs")
     return ap.parse_args()
@@ -162,6 +165,66 @@ def bench_prefill(args, torch, binding, wl):
     }))
 
 
+def bench_migrate(args, torch, binding, wl):
+    """One step = gather of the long requests' pages (all 8 kv heads) into a staging chunk + scatter of that
+    chunk into a target pool with 15 % headroom, i.e. one layer's chunk of a migration on one GPU."""
+    w = wl.WORKLOADS[3]
+    inp = wl.make_inputs(w, device="cuda")
+    lens = inp.context_lens_host
+    rows = np.nonzero(lens >= 8192)[0].astype(np.int32)
+    mlens = lens[rows]
+    m = binding.KvMigration(mlens, rows, w.page_size)
+    n = m.num_pages
+    shape = (n, w.num_kv_heads, w.page_size, w.head_dim)
+    k_stage = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    v_stage = torch.empty_like(k_stage)
+    pool_pages = int(np.ceil(1.15 * n))
+    perm = wl.CounterRng(w.seed + 55).permutation(pool_pages)[:n]
+    need = wl.pages_needed(mlens, w.page_size)
+    tt = np.full((len(rows), int(need.max())), -1, dtype=np.int32)
+    off = np.concatenate([[0], np.cumsum(need)])
+    for r in range(len(rows)):
+        tt[r, : need[r]] = perm[off[r]: off[r + 1]]
+    tt_dev = torch.from_numpy(tt).cuda()
+    k_dst = torch.empty((pool_pages,) + shape[1:], dtype=torch.bfloat16, device="cuda")
+    v_dst = torch.empty_like(k_dst)
+    payload = 2 * n * w.num_kv_heads * w.page_size * w.head_dim * 2     # K and V bytes of the chunk
+
+    def step():
+        m.gather(inp.k_pages, inp.v_pages, inp.block_table, 0, w.num_kv_heads, k_stage, v_stage)
+        m.scatter(k_stage, v_stage, tt_dev, 0, k_dst, v_dst)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    m.enable_timing(True)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = max(wall_ms, start.elapsed_time(stop)) / args.steps
+    kernel_ms, cnt = m.kernel_ms()
+    m.enable_timing(False)
+    moved = 2 * payload                                    # every byte is read once and written once
+    value = 2 * moved / (ms_per_step * 1e-3) / 1e9         # two copies per step
+    achieved = moved / (kernel_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "KV-block migration copy GB/s (bytes read + written)", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"the {len(rows)} long requests of cfg3 ({int(mlens.sum())} tokens, {n} pages, "
+                               f"{payload / 1e9:.3f} GB of K+V per layer chunk): gather to staging + scatter to a target pool"},
+        "roofline": {"bound": "hbm", "kernel": "kv_migrate_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_kernel_ms": round(kernel_ms, 5), "launches_timed": cnt,
+                     "algorithmic_bytes_per_launch": moved},
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -185,6 +248,9 @@ def main():
         return
     if args.prefill >= 0:
         bench_prefill(args, torch, binding, wl)
+        return
+    if args.migrate:
+        bench_migrate(args, torch, binding, wl)
         return
     w = wl.WORKLOADS[args.config]
     sets, nbytes = build_inputs(w, wl, torch)

@@ -247,6 +247,60 @@ oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const voi
 oserve_status_t oserve_prefill_plan_enable_timing(oserve_prefill_plan_t* plan, int32_t enable);
 oserve_status_t oserve_prefill_plan_kernel_ms(oserve_prefill_plan_t* plan, float* mean_ms, int32_t* count);
 
+
+/* ---------------------------------------------------------------------------
+ * KV-block migration copies (paper section 5.2, "KV cache transmission": at a
+ * deployment switch the KV blocks of long requests are migrated in batched,
+ * layer-aligned chunks into buffers pre-allocated on the target, which may hold
+ * a different share of the kv heads).  One layer's chunk, on one GPU:
+ *
+ *   gather : stage[s][j][:][:] = pool[table[row_r][s - first_r]][head_begin + j][:][:]
+ *   scatter: pool[target_table[r][s - first_r]][head_begin + j][:][:] = stage[s][j][:][:]
+ *
+ * for every migrating request r (in the order given at creation), staging page
+ * s in [first_r, first_r + ceil(L_r / page_size)) and copied head j in
+ * [0, num_heads).  Pools are bf16 [pages, pool_kv_heads, page_size, head_dim],
+ * staging chunks bf16 [num_pages, num_heads, page_size, head_dim], both for K
+ * and for V.  Pure data movement: results are bit-exact.
+ * ------------------------------------------------------------------------- */
+typedef struct oserve_kv_migration oserve_kv_migration_t;
+
+/*
+ * The migrating requests.  Host-only except for a small device copy of the two
+ * index arrays, allocated here and owned by the object (this call synchronises).
+ *   context_lens_host  [num_requests] int32 host: L_r >= 1
+ *   table_rows_host    [num_requests] int32 host: row of request r in the SOURCE block table
+ *   device_id          -1 = host object only (cannot launch)
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_CONTEXT_LEN, OSERVE_ERR_DEVICE.
+ */
+oserve_status_t oserve_kv_migration_create(const int32_t* context_lens_host, const int32_t* table_rows_host,
+                                           int32_t num_requests, int32_t page_size, int32_t device_id,
+                                           oserve_kv_migration_t** out);
+void oserve_kv_migration_destroy(oserve_kv_migration_t* m);   /* null allowed; launches must have completed */
+int64_t oserve_kv_migration_num_pages(const oserve_kv_migration_t* m);   /* pages of a staging chunk */
+/* First staging page and page count of request r.  Out pointers may be null. */
+oserve_status_t oserve_kv_migration_request(const oserve_kv_migration_t* m, int32_t r, int32_t* first_page,
+                                            int32_t* num_pages);
+/*
+ * Enqueue one copy on `stream` (no allocation, no synchronisation).  Device pointers, 16-byte aligned.
+ * gather reads rows table_rows_host[r] of `block_table`; scatter reads row r of `target_block_table`.
+ * max_pages_per_seq is the row stride of the table and must cover the longest migrating request.
+ * Pages the tables do not name, and heads outside [head_begin, head_begin + num_heads), are not touched.
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_PLAN_MISMATCH, OSERVE_ERR_DEVICE.
+ * Table entries outside the pool, or two requests naming one target page: undefined.
+ */
+oserve_status_t oserve_kv_gather(oserve_kv_migration_t* m, const void* k_pool, const void* v_pool,
+                                 const int32_t* block_table, int32_t max_pages_per_seq, int32_t pool_kv_heads,
+                                 int32_t head_begin, int32_t num_heads, int32_t head_dim, void* k_stage,
+                                 void* v_stage, void* stream);
+oserve_status_t oserve_kv_scatter(oserve_kv_migration_t* m, const void* k_stage, const void* v_stage,
+                                  const int32_t* target_block_table, int32_t max_pages_per_seq,
+                                  int32_t pool_kv_heads, int32_t head_begin, int32_t num_heads, int32_t head_dim,
+                                  void* k_pool, void* v_pool, void* stream);
+/* Optional timing of the copy kernel (latest launch folded into a running mean), as for the other kernels. */
+oserve_status_t oserve_kv_migration_enable_timing(oserve_kv_migration_t* m, int32_t enable);
+oserve_status_t oserve_kv_migration_kernel_ms(oserve_kv_migration_t* m, float* mean_ms, int32_t* count);
+
 #ifdef __cplusplus
 }
 #endif

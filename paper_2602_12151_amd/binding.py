@@ -73,6 +73,21 @@ def _load() -> ctypes.CDLL:
     lib.oserve_prefill_plan_enable_timing.argtypes = [vp, i32]
     lib.oserve_prefill_plan_kernel_ms.restype = ctypes.c_int
     lib.oserve_prefill_plan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
+    lib.oserve_kv_migration_create.restype = ctypes.c_int
+    lib.oserve_kv_migration_create.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(vp)]
+    lib.oserve_kv_migration_destroy.restype = None
+    lib.oserve_kv_migration_destroy.argtypes = [vp]
+    lib.oserve_kv_migration_num_pages.restype = i64
+    lib.oserve_kv_migration_num_pages.argtypes = [vp]
+    lib.oserve_kv_migration_request.restype = ctypes.c_int
+    lib.oserve_kv_migration_request.argtypes = [vp, i32, pi32, pi32]
+    for name in ("oserve_kv_gather", "oserve_kv_scatter"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.oserve_kv_migration_enable_timing.restype = ctypes.c_int
+    lib.oserve_kv_migration_enable_timing.argtypes = [vp, i32]
+    lib.oserve_kv_migration_kernel_ms.restype = ctypes.c_int
+    lib.oserve_kv_migration_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
     lib.oserve_status_string.restype = ctypes.c_char_p
     lib.oserve_status_string.argtypes = [ctypes.c_int]
     return lib
@@ -316,3 +331,72 @@ def paged_prefill_attn(plan: PrefillPlan, q: torch.Tensor, k_pages: torch.Tensor
     if st != OK:
         raise OserveError(st, "oserve_paged_prefill_attn")
     return out
+
+
+class KvMigration:
+    """Owns an oserve_kv_migration_t*.  Mirrors oserve_kv_migration_* / oserve_kv_gather / oserve_kv_scatter."""
+
+    def __init__(self, context_lens_host, table_rows_host, page_size: int, device_id: int = 0):
+        lens, rows = _host_lens(context_lens_host), _host_lens(table_rows_host)
+        if lens.shape != rows.shape:
+            raise ValueError("context_lens_host and table_rows_host must have the same length")
+        self._h = ctypes.c_void_p()
+        st = lib.oserve_kv_migration_create(lens.ctypes.data, rows.ctypes.data, len(lens), page_size, device_id,
+                                            ctypes.byref(self._h))
+        if st != OK:
+            self._h = ctypes.c_void_p()
+            raise OserveError(st, "oserve_kv_migration_create")
+
+    @property
+    def num_pages(self) -> int:
+        return lib.oserve_kv_migration_num_pages(self._h)
+
+    def request(self, r: int):
+        a, b = ctypes.c_int32(), ctypes.c_int32()
+        st = lib.oserve_kv_migration_request(self._h, r, ctypes.byref(a), ctypes.byref(b))
+        if st != OK:
+            raise OserveError(st, "oserve_kv_migration_request")
+        return a.value, b.value
+
+    def _run(self, fn, name, a_k, a_v, table, pool_heads, head_begin, num_heads, head_dim, b_k, b_v, stream):
+        for t in (a_k, a_v, b_k, b_v, table):
+            if not (t.is_cuda and t.is_contiguous()):
+                raise ValueError("tensors must be contiguous device tensors")
+        if table.dtype != torch.int32:
+            raise TypeError("block table must be int32")
+        s = torch.cuda.current_stream(a_k.device) if stream is None else stream
+        st = fn(self._h, _ptr(a_k), _ptr(a_v), _ptr(table), table.shape[1], pool_heads, head_begin, num_heads,
+                head_dim, _ptr(b_k), _ptr(b_v), ctypes.c_void_p(s.cuda_stream))
+        if st != OK:
+            raise OserveError(st, name)
+
+    def gather(self, k_pool, v_pool, block_table, head_begin: int, num_heads: int, k_stage, v_stage, stream=None):
+        if k_stage.shape != (self.num_pages, num_heads) + tuple(k_pool.shape[2:]) or v_stage.shape != k_stage.shape:
+            raise ValueError("staging chunk must be [num_pages, num_heads, page_size, head_dim]")
+        self._run(lib.oserve_kv_gather, "oserve_kv_gather", k_pool, v_pool, block_table, k_pool.shape[1],
+                  head_begin, num_heads, k_pool.shape[3], k_stage, v_stage, stream)
+
+    def scatter(self, k_stage, v_stage, target_block_table, head_begin: int, k_pool, v_pool, stream=None):
+        if k_stage.shape[0] != self.num_pages or tuple(k_stage.shape[2:]) != tuple(k_pool.shape[2:]):
+            raise ValueError("staging chunk does not match the plan or the pool")
+        self._run(lib.oserve_kv_scatter, "oserve_kv_scatter", k_stage, v_stage, target_block_table,
+                  k_pool.shape[1], head_begin, k_stage.shape[1], k_pool.shape[3], k_pool, v_pool, stream)
+
+    def enable_timing(self, enable: bool = True) -> None:
+        st = lib.oserve_kv_migration_enable_timing(self._h, int(enable))
+        if st != OK:
+            raise OserveError(st, "oserve_kv_migration_enable_timing")
+
+    def kernel_ms(self):
+        ms, n = ctypes.c_float(), ctypes.c_int32()
+        st = lib.oserve_kv_migration_kernel_ms(self._h, ctypes.byref(ms), ctypes.byref(n))
+        if st != OK:
+            raise OserveError(st, "oserve_kv_migration_kernel_ms")
+        return ms.value, n.value
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) and self._h.value and lib is not None:
+            lib.oserve_kv_migration_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = destroy

@@ -78,4 +78,25 @@ struct PrefillParams {
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
                           hipEvent_t start, hipEvent_t stop);
 
+// ---- KV-block migration copies (migrate.hip) ----
+struct MigrateParams {
+    const void* k_src;            // gather: page pool; scatter: staging chunk
+    const void* v_src;
+    void* k_dst;                  // gather: staging chunk; scatter: page pool
+    void* v_dst;
+    const int32_t* block_table;   // names the pool pages (source table for gather, target table for scatter)
+    int32_t table_stride;         // entries per table row
+    const int32_t* table_rows;    // [num_requests] row of each migrating request, or null: row r
+    const int32_t* page_offsets;  // [num_requests + 1] first staging page of each request
+    int32_t num_requests;
+    int64_t num_pages;            // staging pages = page_offsets[num_requests]
+    int32_t pool_heads;           // kv heads per page in the pool
+    int32_t head_begin;           // first pool head of the copied range
+    int32_t num_heads;            // heads copied (= heads per page of the staging chunk)
+    int32_t unit_chunks;          // 16-byte chunks per (page, head): page_size * head_dim * 2 / 16
+};
+
+hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, int num_cus, hipStream_t stream,
+                             hipEvent_t start, hipEvent_t stop);
+
 }  // namespace oserve

@@ -1,0 +1,137 @@
+"""KV-block migration copies: pins of the numpy oracle (CPU) and bit-exact GPU parity."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_migration_oracle as mo
+from paper_2602_12151_amd import binding, workloads as wl
+
+
+# ---------------------------------------------------------------------------- oracle pins (CPU)
+def small_pool(pages=7, heads=3, page_size=16, d=8, seed=0):
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, 65535, size=(pages, heads, page_size, d), dtype=np.uint16)
+
+
+def test_hand_written_example():
+    """Two requests (17 and 16 tokens, page 16): staging = pages [5, 2] of request row 1, then page [4] of row 0."""
+    pool = small_pool()
+    table = np.array([[4, -1], [5, 2]], dtype=np.int32)
+    stage = mo.gather(pool, table, [1, 0], [17, 16], head_begin=1, num_heads=2)
+    assert stage.shape == (3, 2, 16, 8)
+    assert np.array_equal(stage[0], pool[5, 1:3])
+    assert np.array_equal(stage[1], pool[2, 1:3])
+    assert np.array_equal(stage[2], pool[4, 1:3])
+    assert list(mo.staging_offsets([17, 16], 16)) == [0, 2, 3]
+
+
+def test_full_gather_is_the_pool_reindexed_and_head_ranges_compose():
+    pool = small_pool(pages=10, heads=4)
+    table = np.array([[9, 3, 1], [0, 7, -1]], dtype=np.int32)
+    lens = [48, 20]
+    full = mo.gather(pool, table, [0, 1], lens, 0, 4)
+    assert np.array_equal(full, pool[[9, 3, 1, 0, 7]])
+    lo = mo.gather(pool, table, [0, 1], lens, 0, 2)
+    hi = mo.gather(pool, table, [0, 1], lens, 2, 2)
+    assert np.array_equal(np.concatenate([lo, hi], axis=1), full)
+
+
+def test_scatter_restores_gathered_pages_and_touches_nothing_else():
+    pool = small_pool(pages=10, heads=4, seed=1)
+    table = np.array([[9, 3, 1], [0, 7, -1]], dtype=np.int32)
+    lens = [48, 20]
+    stage = mo.gather(pool, table, [0, 1], lens, 1, 2)
+    blank = np.full_like(pool, 0xABCD)
+    out = mo.scatter(stage, blank, table, lens, 1)
+    named = [9, 3, 1, 0, 7]
+    assert np.array_equal(out[named][:, 1:3], pool[named][:, 1:3])
+    assert (out[named][:, 0] == 0xABCD).all() and (out[named][:, 3] == 0xABCD).all()
+    others = [p for p in range(10) if p not in named]
+    assert (out[others] == 0xABCD).all()
+
+
+def test_plan_offsets_through_the_c_abi():
+    lens = [17, 16, 1, 4000]
+    m = binding.KvMigration(lens, [3, 0, 2, 1], 16, device_id=-1)
+    off = mo.staging_offsets(lens, 16)
+    assert m.num_pages == off[-1]
+    for r in range(4):
+        assert m.request(r) == (off[r], off[r + 1] - off[r])
+    with pytest.raises(binding.OserveError):
+        binding.KvMigration([0], [0], 16, device_id=-1)
+    with pytest.raises(binding.OserveError):
+        binding.KvMigration([5], [0], 48, device_id=-1)
+
+
+# ---------------------------------------------------------------------------- GPU parity (bit-exact)
+def _bits(t):
+    return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("page_size,d", [(16, 128), (64, 128), (32, 64)])
+def test_gpu_gather_and_scatter_are_bit_exact(page_size, d):
+    """Source pool with 8 kv heads; the long requests migrate to a target pool that holds 4 heads per page
+    (a target deployment of twice the tensor-parallel degree): heads 4..7 of the source become heads 0..3."""
+    lens = np.array([40, 9000, 517, 20000, 16, 1300, 31000], dtype=np.int32)
+    w = wl.Workload(9, "migrate", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=d, page_size=page_size)
+    src = wl.make_inputs(w, device="cuda", seed=page_size + d, lens=lens)
+    long_rows = np.array([3, 1, 6], dtype=np.int32)               # migrate the three longest, in this order
+    mlens = lens[long_rows]
+    m = binding.KvMigration(mlens, long_rows, page_size)
+    n = m.num_pages
+    k_stage = torch.zeros((n, 4, page_size, d), dtype=torch.bfloat16, device="cuda")
+    v_stage = torch.zeros_like(k_stage)
+    m.gather(src.k_pages, src.v_pages, src.block_table, 4, 4, k_stage, v_stage)
+    torch.cuda.synchronize()
+    bt = src.block_table.cpu().numpy()
+    assert np.array_equal(_bits(k_stage), mo.gather(_bits(src.k_pages), bt, long_rows, mlens, 4, 4))
+    assert np.array_equal(_bits(v_stage), mo.gather(_bits(src.v_pages), bt, long_rows, mlens, 4, 4))
+
+    # target: 4 heads per page, pool with 15 % headroom, its own page assignment
+    rng = wl.CounterRng(7)
+    pool_pages = int(np.ceil(1.15 * n))
+    perm = rng.permutation(pool_pages)[:n]
+    width = int(wl.pages_needed(mlens, page_size).max())
+    tt = np.full((len(mlens), width), -1, dtype=np.int32)
+    off = mo.staging_offsets(mlens, page_size)
+    for r in range(len(mlens)):
+        tt[r, : off[r + 1] - off[r]] = perm[off[r]: off[r + 1]]
+    k_dst = torch.full((pool_pages, 4, page_size, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    v_dst = torch.full_like(k_dst, -3.0)
+    before_k, before_v = _bits(k_dst).copy(), _bits(v_dst).copy()
+    m.scatter(k_stage, v_stage, torch.from_numpy(tt).cuda(), 0, k_dst, v_dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(k_dst), mo.scatter(_bits(k_stage), before_k, tt, mlens, 0))
+    assert np.array_equal(_bits(v_dst), mo.scatter(_bits(v_stage), before_v, tt, mlens, 0))
+
+
+@pytest.mark.gpu
+def test_gpu_migrated_requests_attend_identically_on_the_target():
+    """End to end on one GPU: after gather + scatter of all heads, decode attention of the migrated requests
+    over the target pool is bit-identical to decode attention over the source pool."""
+    from tests import gpu_helpers as gh
+    lens = np.array([300, 5000, 77, 12000], dtype=np.int32)
+    w = wl.Workload(9, "migrate", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    src = wl.make_inputs(w, device="cuda", seed=21, lens=lens)
+    rows = np.array([1, 3], dtype=np.int32)
+    mlens = lens[rows]
+    m = binding.KvMigration(mlens, rows, 16)
+    n = m.num_pages
+    ks = torch.empty((n, 8, 16, 128), dtype=torch.bfloat16, device="cuda")
+    vs = torch.empty_like(ks)
+    m.gather(src.k_pages, src.v_pages, src.block_table, 0, 8, ks, vs)
+    perm = wl.CounterRng(3).permutation(n + 5)[:n]
+    off = mo.staging_offsets(mlens, 16)
+    tt = np.full((2, int(wl.pages_needed(mlens).max())), -1, dtype=np.int32)
+    for r in range(2):
+        tt[r, : off[r + 1] - off[r]] = perm[off[r]: off[r + 1]]
+    kd = torch.zeros((n + 5, 8, 16, 128), dtype=torch.bfloat16, device="cuda")
+    vd = torch.zeros_like(kd)
+    m.scatter(ks, vs, torch.from_numpy(tt).cuda(), 0, kd, vd)
+    dst = wl.Inputs(workload=w, q=src.q[torch.from_numpy(rows).long().cuda()].contiguous(), k_pages=kd, v_pages=vd,
+                    block_table=torch.from_numpy(tt).cuda(), context_lens=torch.from_numpy(mlens.copy()).cuda(),
+                    context_lens_host=mlens, scale=src.scale, used_pages=perm)
+    out_dst, _ = gh.gpu_attention(dst, split_tokens=1024)
+    out_src, _ = gh.gpu_attention(src, split_tokens=1024)
+    assert torch.equal(out_dst, out_src[torch.from_numpy(rows).long().cuda()])
