@@ -301,6 +301,65 @@ oserve_status_t oserve_kv_scatter(oserve_kv_migration_t* m, const void* k_stage,
 oserve_status_t oserve_kv_migration_enable_timing(oserve_kv_migration_t* m, int32_t enable);
 oserve_status_t oserve_kv_migration_kernel_ms(oserve_kv_migration_t* m, float* mean_ms, int32_t* count);
 
+
+/* ---------------------------------------------------------------------------
+ * Host-side planners of the serving method (no GPU work; every pointer is a
+ * HOST pointer).
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Greedy switch plan (paper section 5.2 and the appendix "Greedy Algorithm for Ad
+ * Hoc Model Switching"): for every model shard m and every target device t that
+ * needs m and does not hold it, choose the source device that sends it.  Sources
+ * on t's machine are preferred to sources on other machines; among the candidates
+ * the one with the least volume already planned from it to t is chosen (the first
+ * listed among equals), and the pair's counter grows by the shard's volume.
+ * Shards are processed in index order, targets in the order listed.
+ *
+ *   device_machine   [num_devices] machine index of each device
+ *   source_offsets   [num_shards + 1], source_devices: the devices holding shard m are
+ *                    source_devices[source_offsets[m] .. source_offsets[m+1])
+ *   target_offsets   [num_shards + 1], target_devices, volumes: likewise the devices that
+ *                    need shard m and the volume of each such (m, t) requirement
+ *   chosen_source    out, aligned with target_devices: the chosen source, or -1 where the
+ *                    target already holds the shard
+ *   pair_load        out or null: [num_devices x num_devices] planned volume from s (row) to t
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (bad index, negative volume, a needed shard nobody holds).
+ */
+oserve_status_t oserve_switch_plan(int32_t num_devices, const int32_t* device_machine, int32_t num_shards,
+                                   const int32_t* source_offsets, const int32_t* source_devices,
+                                   const int32_t* target_offsets, const int32_t* target_devices,
+                                   const int64_t* volumes, int32_t* chosen_source, int64_t* pair_load);
+
+/*
+ * Edge capacity normalisation (section 4.1): the common capacity M of a replica that
+ * can process per_type_capacity[j] requests of type j per unit time alone is the least
+ * common multiple of those numbers (zeros = types it cannot serve are skipped); one
+ * type-j request then consumes units_per_request[j] = M / per_type_capacity[j] units.
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (negative capacity, overflow of 64 bits).
+ */
+oserve_status_t oserve_capacity_normalise(const int64_t* per_type_capacity, int32_t num_types, int64_t* common,
+                                          int64_t* units_per_request);
+
+/*
+ * Lower-level workload assignment (section 4.1): the assignment x[k][j] >= 0 of type-j
+ * requests to replica k that serves the most requests subject to
+ *   C1  sum_k x[k][j] <= arrivals[j]
+ *   C2  x[k][j] <= edge_capacity[k][j]                 (skipped when edge_capacity is null or infinite)
+ *   C3  sum_j x[k][j] * M_k / node_capacity[k][j] <= M_k   (M_k as in oserve_capacity_normalise)
+ * Because the types consume different shares of a replica per request, this flow
+ * problem is a linear program; it is solved exactly (simplex).  The optimum value
+ * `total` is unique; the assignment attaining it need not be.
+ *   arrivals       [num_types]
+ *   node_capacity  [num_replicas x num_types] int64, 0 = replica cannot serve the type
+ *   edge_capacity  [num_replicas x num_types] or null
+ *   assignment     out [num_replicas x num_types], total: out
+ * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (negative or non-finite input, more than 4096 pairs).
+ */
+oserve_status_t oserve_assign_workload(int32_t num_replicas, int32_t num_types, const double* arrivals,
+                                       const int64_t* node_capacity, const double* edge_capacity,
+                                       double* assignment, double* total);
+
 #ifdef __cplusplus
 }
 #endif

@@ -88,6 +88,12 @@ def _load() -> ctypes.CDLL:
     lib.oserve_kv_migration_enable_timing.argtypes = [vp, i32]
     lib.oserve_kv_migration_kernel_ms.restype = ctypes.c_int
     lib.oserve_kv_migration_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
+    lib.oserve_switch_plan.restype = ctypes.c_int
+    lib.oserve_switch_plan.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.oserve_capacity_normalise.restype = ctypes.c_int
+    lib.oserve_capacity_normalise.argtypes = [vp, i32, ctypes.POINTER(i64), vp]
+    lib.oserve_assign_workload.restype = ctypes.c_int
+    lib.oserve_assign_workload.argtypes = [i32, i32, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.oserve_status_string.restype = ctypes.c_char_p
     lib.oserve_status_string.argtypes = [ctypes.c_int]
     return lib
@@ -400,3 +406,57 @@ class KvMigration:
             self._h = ctypes.c_void_p()
 
     __del__ = destroy
+
+
+def switch_plan(device_machine, sources, targets, volumes):
+    """oserve_switch_plan on Python lists: sources[m] / targets[m] list the devices holding / needing shard m,
+    volumes[m][i] is the volume of (m, targets[m][i]).  Returns (chosen sources per shard, pair-load matrix)."""
+    dm = np.ascontiguousarray(device_machine, dtype=np.int32)
+    so = np.zeros(len(sources) + 1, dtype=np.int32)
+    to = np.zeros(len(targets) + 1, dtype=np.int32)
+    so[1:] = np.cumsum([len(x) for x in sources])
+    to[1:] = np.cumsum([len(x) for x in targets])
+    sd = np.ascontiguousarray([d for x in sources for d in x], dtype=np.int32)
+    td = np.ascontiguousarray([d for x in targets for d in x], dtype=np.int32)
+    vol = np.ascontiguousarray([v for x in volumes for v in x], dtype=np.int64)
+    if len(vol) != len(td):
+        raise ValueError("volumes must align with targets")
+    chosen = np.full(max(len(td), 1), -2, dtype=np.int32)
+    load = np.zeros((len(dm), len(dm)), dtype=np.int64)
+    pad = np.zeros(1, dtype=np.int32)
+    st = lib.oserve_switch_plan(len(dm), dm.ctypes.data, len(sources), so.ctypes.data,
+                                (sd if len(sd) else pad).ctypes.data, to.ctypes.data,
+                                (td if len(td) else pad).ctypes.data,
+                                (vol if len(vol) else np.zeros(1, dtype=np.int64)).ctypes.data,
+                                chosen.ctypes.data, load.ctypes.data)
+    if st != OK:
+        raise OserveError(st, "oserve_switch_plan")
+    return [list(map(int, chosen[to[m]:to[m + 1]])) for m in range(len(targets))], load
+
+
+def capacity_normalise(per_type_capacity):
+    n = np.ascontiguousarray(per_type_capacity, dtype=np.int64)
+    m = ctypes.c_int64()
+    units = np.zeros(len(n), dtype=np.int64)
+    st = lib.oserve_capacity_normalise(n.ctypes.data, len(n), ctypes.byref(m), units.ctypes.data)
+    if st != OK:
+        raise OserveError(st, "oserve_capacity_normalise")
+    return m.value, [int(u) for u in units]
+
+
+def assign_workload(arrivals, node_capacity, edge_capacity=None):
+    """oserve_assign_workload: returns (total requests served, assignment [replicas, types])."""
+    lam = np.ascontiguousarray(arrivals, dtype=np.float64)
+    n = np.ascontiguousarray(node_capacity, dtype=np.int64)
+    if n.ndim != 2 or n.shape[1] != len(lam):
+        raise ValueError("node_capacity must be [replicas, types]")
+    e = None if edge_capacity is None else np.ascontiguousarray(edge_capacity, dtype=np.float64)
+    if e is not None and e.shape != n.shape:
+        raise ValueError("edge_capacity must match node_capacity")
+    x = np.zeros(n.shape, dtype=np.float64)
+    total = ctypes.c_double()
+    st = lib.oserve_assign_workload(n.shape[0], n.shape[1], lam.ctypes.data, n.ctypes.data,
+                                    None if e is None else e.ctypes.data, x.ctypes.data, ctypes.byref(total))
+    if st != OK:
+        raise OserveError(st, "oserve_assign_workload")
+    return total.value, x
