@@ -42,7 +42,7 @@ struct oserve_prefill_plan {
         while ((1 << s) < geo.group()) ++s;
         return s;
     }
-    int32_t block_tokens() const { return 4 * (64 >> group_shift()); }   // query tokens per workgroup
+    int32_t block_tokens() const { return oserve::prefill_block_tokens(group_shift()); }   // query tokens per workgroup
     int64_t max_items() const {
         return (max_query_tokens / block_tokens() + capacity) * geo.num_kv_heads;
     }

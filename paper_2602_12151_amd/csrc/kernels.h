@@ -52,6 +52,21 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
 // ---- chunked prefill (prefill.hip) ----
+#ifndef OSERVE_PF_WAVES
+#define OSERVE_PF_WAVES 8
+#endif
+#ifndef OSERVE_PF_MACRO
+#define OSERVE_PF_MACRO 64
+#endif
+constexpr int kPrefillWaves = OSERVE_PF_WAVES;    // wavefronts per workgroup
+#ifndef OSERVE_PF_CT
+#define OSERVE_PF_CT 2
+#endif
+constexpr int kPrefillColTiles = OSERVE_PF_CT;    // 16-column score tiles per wavefront
+constexpr int kPrefillMacroKeys = OSERVE_PF_MACRO;  // keys staged in LDS per barrier
+// query tokens of one work item for a GQA group of 1 << group_shift heads
+inline int prefill_block_tokens(int group_shift) { return kPrefillWaves * ((16 * kPrefillColTiles) >> group_shift); }
+
 // One workgroup's work: a block of query tokens of one request against one kv head.
 struct PrefillItem {
     int32_t request;       // index into block_table rows

@@ -43,14 +43,13 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-constexpr int kPrefillWaves = 8;
 constexpr int kPrefillThreads = 64 * kPrefillWaves;
-constexpr int kColTiles = 2;        // 16-column tiles per wavefront
+constexpr int kColTiles = kPrefillColTiles;
 constexpr int kStepKeys = 32;
-constexpr int kMacroKeys = 128;     // keys staged in LDS per barrier
+constexpr int kMacroKeys = kPrefillMacroKeys;
 
 template <int D>
-__global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void paged_prefill_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4))) void paged_prefill_kernel(const PrefillParams p) {
     static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
     constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
@@ -113,25 +112,27 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     };
 
     // ---- staging: per macro step the workgroup copies kMacroKeys / 16 K tiles and as many V tiles
-    // of 4 KB; thread t copies bytes [16 t', 16 t' + 16), t' = t % 256, of tiles t / 256 + 2 i ----
-    uint4 stage[SUB][2];
-    const int st_half = tid >> 8;
+    // of 4 KB; thread t copies bytes [16 t', 16 t' + 16), t' = t % 256, of tiles t / 256 + TPI * i ----
+    constexpr int TPI = kPrefillThreads / 256;          // tiles copied per pass of the workgroup
+    constexpr int NIT = (kMacroKeys / 16) / TPI;        // passes per macro step
+    uint4 stage[NIT][2];
+    const int st_tile = tid >> 8;
     const int st_key = (tid & 255) >> 4;   // key within the 16-key tile
     const int st_col = tid & 15;           // 16-byte chunk within the key's row
     auto prefetch = [&](int macro) {
 #pragma unroll
-        for (int i = 0; i < SUB; ++i) {
-            const int64_t base = tile_base_of((kMacroKeys / 16) * macro + 2 * i + st_half) + (tid & 255) * 8;
+        for (int i = 0; i < NIT; ++i) {
+            const int64_t base = tile_base_of((kMacroKeys / 16) * macro + TPI * i + st_tile) + (tid & 255) * 8;
             stage[i][0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
             stage[i][1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
         }
     };
     auto commit = [&](int macro, int buf) {
 #pragma unroll
-        for (int i = 0; i < SUB; ++i) {
+        for (int i = 0; i < NIT; ++i) {
             // keys at or beyond the context may hold anything: zero them (a NaN there would
             // survive a zero probability in the value product)
-            const int row = 32 * i + 16 * st_half + st_key;
+            const int row = 16 * (TPI * i + st_tile) + st_key;
             const bool live = kMacroKeys * macro + row < L;
             const uint4 z = make_uint4(0u, 0u, 0u, 0u);
             const int off = row * ROW + st_col * 16;
