@@ -11,10 +11,10 @@
 // wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
 //   * the wavefronts copy K and V tiles of kMacroKeys keys from the page pool into LDS with coalesced
-//     16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free),
-//     double-buffered, one barrier per kMacroKeys keys: between two barriers the wavefronts drift
-//     apart, so that one's MFMAs overlap another's softmax arithmetic; the loads of the next
-//     macro step are in flight during the current one;
+//     16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free), one barrier
+//     per kMacroKeys keys; the loads of the next macro step are in flight during the current one;
+//     half of the wavefronts run their softmax and value phases one macro step late, so that on
+//     every SIMD one wavefront's MFMAs overlap the other's softmax arithmetic;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
 //   * online softmax in the log2 domain, one update per column and macro step, per-column state
@@ -57,7 +57,8 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     constexpr int TILE = kMacroKeys * ROW;
     constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
     constexpr int CT = kColTiles;
-    __shared__ __align__(16) unsigned char lds[2][2][TILE];   // [buffer][K, V]
+    __shared__ __align__(16) unsigned char lds_k[2][TILE];   // K tiles: double-buffered
+    __shared__ __align__(16) unsigned char lds_v[3][TILE];   // V tiles: one more, for the wavefronts that run a macro step late
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -119,15 +120,21 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const int st_tile = tid >> 8;
     const int st_key = (tid & 255) >> 4;   // key within the 16-key tile
     const int st_col = tid & 15;           // 16-byte chunk within the key's row
-    auto prefetch = [&](int macro) {
+    // page ids are fetched (scalar loads) one macro step before the tile loads that need them
+    int64_t next_base[NIT];
+    auto fetch_bases = [&](int macro) {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) next_base[i] = tile_base_of((kMacroKeys / 16) * macro + TPI * i + st_tile);
+    };
+    auto prefetch = [&]() {   // tile loads of the macro step whose bases were fetched last
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int64_t base = tile_base_of((kMacroKeys / 16) * macro + TPI * i + st_tile) + (tid & 255) * 8;
+            const int64_t base = next_base[i] + (tid & 255) * 8;
             stage[i][0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
             stage[i][1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
         }
     };
-    auto commit = [&](int macro, int buf) {
+    auto commit = [&](int macro) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             // keys at or beyond the context may hold anything: zero them (a NaN there would
@@ -136,8 +143,8 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             const bool live = kMacroKeys * macro + row < L;
             const uint4 z = make_uint4(0u, 0u, 0u, 0u);
             const int off = row * ROW + st_col * 16;
-            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = live ? stage[i][0] : z;
-            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = live ? stage[i][1] : z;
+            *reinterpret_cast<uint4*>(&lds_k[macro & 1][off]) = live ? stage[i][0] : z;
+            *reinterpret_cast<uint4*>(&lds_v[macro % 3][off]) = live ? stage[i][1] : z;
         }
     };
 
@@ -150,13 +157,12 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) { m[ct] = -INFINITY; l[ct] = 0.f; }
 
-    // One macro step for this wavefront's 16*CT columns, in three phases so that the MFMAs of a
+    // One macro step for this wavefront's 16*CT columns runs in three phases, so that the MFMAs of a
     // phase are issued back to back: (1) all scores of the kMacroKeys keys, (2) one online-softmax
     // update per column over all of them, (3) the value products.
-    auto compute = [&](int macro, int buf, auto masked) {
-        const unsigned char* kt = lds[buf][0];
-        const unsigned char* vt = lds[buf][1];
-        f32x4 s[SUB][CT][2];
+    f32x4 s[SUB][CT][2];     // scores; lane (i16, g4) holds, for column i16 of tile ct, keys 32*sub + 16*h + 4*g4 + r
+    auto scores = [&](int macro) __attribute__((always_inline)) {
+        const unsigned char* kt = lds_k[macro & 1];
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
@@ -174,7 +180,8 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                     s[sub][ct][h] = a;
                 }
             }
-        // lane (i16, g4) holds, for column i16 of each tile, keys 32*sub + 16*h + 4*g4 + r
+    };
+    auto softmax_and_values = [&](int macro, auto masked) __attribute__((always_inline)) {
         bf16x8 pb[SUB][CT];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
@@ -220,6 +227,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             l[ct] += sum;
         }
         // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4
+        const unsigned char* vt = lds_v[macro % 3];
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub) {
             uint32_t vw[8][4];
@@ -243,24 +251,42 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     };
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
+    // phases 2 and 3 of macro step `macro`, if any of its keys is visible to this wavefront
+    auto finish = [&](int macro) __attribute__((always_inline)) {
+        const int first_key = kMacroKeys * macro;
+        if (first_key + kMacroKeys - 1 > pos_min) softmax_and_values(macro, Masked{});
+        else softmax_and_values(macro, Plain{});
+    };
 
-    // ---- main loop: one barrier per macro step ----
+    // ---- main loop: one barrier per macro step.  The two wavefronts that share a SIMD (w and
+    // w + 4) run out of phase: the late half finishes macro step M-1 (softmax arithmetic, then value
+    // MFMAs) while the early half computes the scores of macro step M (MFMAs, then its softmax), so
+    // that one's VALU phase overlaps the other's MFMA phases.  That is why V has a third LDS buffer.
     const int num_macro = (num_steps + SUB - 1) / SUB;
-    prefetch(0);
-    commit(0, 0);
+    const bool late = (wave & 1) != 0;
+    // macro steps with a key visible to this wavefront: 0 .. my_macros-1
+    const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
+    fetch_bases(0);
+    prefetch();
+    fetch_bases(1);
+    commit(0);
     __syncthreads();
     for (int macro = 0; macro < num_macro; ++macro) {
-        const int buf = macro & 1;
         const bool more = macro + 1 < num_macro;
-        if (more) prefetch(macro + 1);
-        const int first_key = kMacroKeys * macro;
-        if (first_key <= pos_max) {                       // otherwise every key is in this wavefront's future
-            if (first_key + kMacroKeys - 1 > pos_min) compute(macro, buf, Masked{});
-            else compute(macro, buf, Plain{});
+        if (more) {
+            prefetch();                 // tiles of macro + 1
+            fetch_bases(macro + 2);     // clamped to the request's last tile
         }
-        if (more) commit(macro + 1, buf ^ 1);
+        if (!late) {
+            if (macro < my_macros) { scores(macro); finish(macro); }
+        } else {
+            if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1);
+            if (macro < my_macros) scores(macro);
+        }
+        if (more) commit(macro + 1);
         __syncthreads();
     }
+    if (late && num_macro - 1 < my_macros) finish(num_macro - 1);
 
     // ---- write out: lane holds column i16 of each tile, dims 8*(4*g4 + r) + e ----
 #pragma unroll
