@@ -1,0 +1,33 @@
+"""The command-line and import contracts that need no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus 2 exits with a message instead of measuring."""
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, cwd=ROOT, timeout=120)
+    assert proc.returncode == 2
+    assert "one GPU" in proc.stderr and proc.stdout.strip() == ""
+
+
+def test_binding_fails_loudly_without_the_built_library():
+    """No fallback path: with the library missing, importing the binding raises."""
+    code = "import paper_2602_12151_amd.binding"
+    env = dict(os.environ, OSERVE_LIB=os.path.join(ROOT, "does_not_exist", "liboserve.so"))
+    proc = subprocess.run([sys.executable, "-c", code], stdout=subprocess.PIPE, stderr=subprocess.PIPE,
+                          text=True, cwd=ROOT, env=env, timeout=120)
+    assert proc.returncode != 0
+    assert "ImportError" in proc.stderr and "no fallback" in proc.stderr
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2602_12151_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "workloads.py" and "oracle" in text.lower(), f
