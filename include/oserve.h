@@ -199,7 +199,10 @@ const char* oserve_status_string(oserve_status_t status);
 typedef struct oserve_prefill_plan oserve_prefill_plan_t;
 
 /*
- * Plan: the list of work items (block of query tokens x kv head), heaviest first.
+ * Plan: the list of work items (block of query tokens x kv head).  The blocks of one
+ * (request, kv head) read the same K/V; they are placed at launch indices that are
+ * equal modulo 8 so that they run side by side on one of the device's 8 XCDs and
+ * share its L2; (request, kv head) groups are dealt to the XCDs heaviest first.
  * Host-only.  It also owns the pinned staging through which the kernel reads that
  * list (OSERVE_PLAN_RING slots, same reuse rule as the decode plan).
  *

@@ -21,8 +21,13 @@ struct oserve_prefill_plan {
     int32_t device_id = -1;
     int32_t batch = 0;
     int64_t query_tokens = 0;
+    static constexpr int kXcds = 8;  // accelerator dies of the device, each with its own L2
     std::vector<PrefillItem> items;  // launch order
     std::vector<PrefillItem> scratch;
+    std::vector<PrefillItem> per_xcd[kXcds];
+    struct Group { int32_t request, kv_head; int64_t work; };
+    std::vector<Group> groups;
+    std::vector<int64_t> row0;
     // ring of pinned staging slots read directly by the kernel; `done` completes with the kernel
     char* staging = nullptr;
     char* staging_dev = nullptr;
@@ -80,7 +85,7 @@ bool collect(oserve_prefill_plan* pl, int slot) {
     return true;
 }
 
-// Work items: blocks of query tokens x kv heads, heaviest (most keys to visit) first.
+// Work items: blocks of query tokens x kv heads, ordered for L2 reuse and balance (see below).
 oserve_status_t build(oserve_prefill_plan* pl, const int32_t* lens, const int32_t* qlens, int32_t n) {
     if (!lens || !qlens) return OSERVE_ERR_NULL;
     if (n < 1 || n > pl->capacity) return OSERVE_ERR_PLAN_MISMATCH;
@@ -92,21 +97,51 @@ oserve_status_t build(oserve_prefill_plan* pl, const int32_t* lens, const int32_
     }
     if (total_q > pl->max_query_tokens) return OSERVE_ERR_PLAN_MISMATCH;
     const int32_t qb = pl->block_tokens();
+    const int32_t hkv = pl->geo.num_kv_heads;
+    // Groups = (request, kv head): all query blocks of a group read the same K/V.  Workgroups go to
+    // the device's XCDs round-robin by index, and every XCD has its own L2, so the blocks of a group
+    // are placed at indices that are equal modulo the XCD count: they then run side by side on one
+    // XCD and its L2 serves the K/V tiles that the first of them fetched.  Groups are dealt to the
+    // XCDs heaviest first, each to the XCD with the least work so far; inside a group the blocks
+    // with the most keys come first.
+    using Group = oserve_prefill_plan::Group;
+    std::vector<Group>& groups = pl->groups;
+    groups.clear();
+    for (int32_t b = 0; b < n; ++b) {
+        int64_t work = 0;
+        for (int32_t q0 = 0; q0 < qlens[b]; q0 += qb)
+            work += lens[b] - qlens[b] + std::min(q0 + qb, qlens[b]);
+        for (int32_t j = 0; j < hkv; ++j) groups.push_back(Group{b, j, work});
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group& a, const Group& c) { return a.work > c.work; });
+    std::vector<int64_t>& row0 = pl->row0;
+    row0.assign(static_cast<size_t>(n) + 1, 0);
+    for (int32_t b = 0; b < n; ++b) row0[b + 1] = row0[b] + qlens[b];
+    constexpr int kXcds = oserve_prefill_plan::kXcds;
+    int64_t load[kXcds] = {};
+    for (int x = 0; x < kXcds; ++x) pl->per_xcd[x].clear();
+    for (const Group& g : groups) {
+        int best = 0;
+        for (int x = 1; x < kXcds; ++x)
+            if (load[x] < load[best]) best = x;
+        load[best] += g.work;
+        const int32_t b = g.request;
+        const int32_t blocks = (qlens[b] + qb - 1) / qb;
+        for (int32_t k = blocks - 1; k >= 0; --k)     // last blocks see the most keys
+            pl->per_xcd[best].push_back(PrefillItem{b, g.kv_head, k * qb, static_cast<int32_t>(row0[b]), lens[b], qlens[b], {0, 0}});
+    }
+    // interleave: position 8 k + x takes the k-th item of XCD x's list; exhausted lists are skipped
     std::vector<PrefillItem>& it = pl->scratch;
     it.clear();
-    int64_t row0 = 0;
-    for (int32_t b = 0; b < n; ++b) {
-        for (int32_t q0 = 0; q0 < qlens[b]; q0 += qb)
-            for (int32_t j = 0; j < pl->geo.num_kv_heads; ++j)
-                it.push_back(PrefillItem{b, j, q0, static_cast<int32_t>(row0), lens[b], qlens[b], {0, 0}});
-        row0 += qlens[b];
+    size_t cursor[kXcds] = {};
+    for (bool any = true; any;) {
+        any = false;
+        for (int x = 0; x < kXcds; ++x)
+            if (cursor[x] < pl->per_xcd[x].size()) {
+                it.push_back(pl->per_xcd[x][cursor[x]++]);
+                any = true;
+            }
     }
-    auto keys_visited = [qb](const PrefillItem& x) {
-        return x.context_len - x.q_len + std::min(x.q_begin + qb, x.q_len);
-    };
-    std::stable_sort(it.begin(), it.end(), [&](const PrefillItem& a, const PrefillItem& c) {
-        return keys_visited(a) > keys_visited(c);
-    });
     pl->items.swap(it);
     pl->batch = n;
     pl->query_tokens = total_q;
@@ -140,6 +175,9 @@ oserve_status_t oserve_prefill_plan_create(const int32_t* context_lens_host, con
     pl->device_id = device_id;
     pl->items.reserve(static_cast<size_t>(pl->max_items()));
     pl->scratch.reserve(static_cast<size_t>(pl->max_items()));
+    for (auto& v : pl->per_xcd) v.reserve(static_cast<size_t>(pl->max_items()));
+    pl->groups.reserve(static_cast<size_t>(capacity) * num_kv_heads);
+    pl->row0.reserve(static_cast<size_t>(capacity) + 1);
     pl->slot_bytes = (static_cast<size_t>(pl->max_items()) * sizeof(PrefillItem) + 255) & ~static_cast<size_t>(255);
     if (device_id >= 0) {
         int n_dev = 0;
