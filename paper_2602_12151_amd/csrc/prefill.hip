@@ -10,9 +10,12 @@
 // overlap the other's softmax arithmetic) per (request, kv head, block of query tokens).  Every
 // wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
-//   * the wavefronts copy K and V tiles of kMacroKeys keys from the page pool into LDS with coalesced
-//     16-byte loads (rows padded by 16 bytes so that operand reads are conflict-free), one barrier
-//     per kMacroKeys keys; the loads of the next macro step are in flight during the current one;
+//   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
+//     (global_load_lds, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
+//     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
+//     stored XOR-swizzled with the key index (lane l fetches chunk (l % 16) ^ key), which makes
+//     both operand read patterns conflict-free.  One barrier per kMacroKeys keys; the loads of the
+//     next macro step are in flight during the current one;
 //     half of the wavefronts run their softmax and value phases one macro step late, so that on
 //     every SIMD one wavefront's MFMAs overlap the other's softmax arithmetic;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
     constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
-    constexpr int ROW = D * 2 + 16;      // bytes of one key's row in LDS (padded)
+    constexpr int ROW = D * 2;           // bytes of one key's row in LDS; chunk c of key k sits at slot c ^ (k % 16)
     constexpr int TILE = kMacroKeys * ROW;
     constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
     constexpr int CT = kColTiles;
@@ -112,40 +115,30 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (16 * D);
     };
 
-    // ---- staging: per macro step the workgroup copies kMacroKeys / 16 K tiles and as many V tiles
-    // of 4 KB; thread t copies bytes [16 t', 16 t' + 16), t' = t % 256, of tiles t / 256 + TPI * i ----
-    constexpr int TPI = kPrefillThreads / 256;          // tiles copied per pass of the workgroup
-    constexpr int NIT = (kMacroKeys / 16) / TPI;        // passes per macro step
-    uint4 stage[NIT][2];
-    const int st_tile = tid >> 8;
-    const int st_key = (tid & 255) >> 4;   // key within the 16-key tile
-    const int st_col = tid & 15;           // 16-byte chunk within the key's row
+    // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
+    // of 4 KB into LDS.  Wavefront w fetches tile w % TILES of K (w < TILES) or V, one quarter (four
+    // keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk (l % 16) ^ key. ----
+    constexpr int TILES = kMacroKeys / 16;
+    static_assert(kPrefillWaves == 2 * TILES, "one wavefront per staged tile");
+    const int st_tile = wave % TILES;
+    const bool st_is_v = wave >= TILES;
+    const uint16_t* st_pool = st_is_v ? p.v_pages : p.k_pages;
+    int st_lane_off[4];                    // element offset of this lane's chunk within the tile, per quarter
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int key = 4 * q + (lane >> 4);
+        st_lane_off[q] = key * D + (((lane & 15) ^ key) * 8);
+    }
     // page ids are fetched (scalar loads) one macro step before the tile loads that need them
-    int64_t next_base[NIT];
-    auto fetch_bases = [&](int macro) {
+    int64_t next_base;
+    auto fetch_base = [&](int macro) { next_base = tile_base_of(TILES * macro + st_tile); };
+    auto prefetch = [&](int macro) {   // loads of macro step `macro`, whose base was fetched last
+        unsigned char* dst = (st_is_v ? lds_v[macro % 3] : lds_k[macro & 1]) + st_tile * 16 * ROW;
 #pragma unroll
-        for (int i = 0; i < NIT; ++i) next_base[i] = tile_base_of((kMacroKeys / 16) * macro + TPI * i + st_tile);
-    };
-    auto prefetch = [&]() {   // tile loads of the macro step whose bases were fetched last
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int64_t base = next_base[i] + (tid & 255) * 8;
-            stage[i][0] = *reinterpret_cast<const uint4*>(p.k_pages + base);
-            stage[i][1] = *reinterpret_cast<const uint4*>(p.v_pages + base);
-        }
-    };
-    auto commit = [&](int macro) {
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            // keys at or beyond the context may hold anything: zero them (a NaN there would
-            // survive a zero probability in the value product)
-            const int row = 16 * (TPI * i + st_tile) + st_key;
-            const bool live = kMacroKeys * macro + row < L;
-            const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-            const int off = row * ROW + st_col * 16;
-            *reinterpret_cast<uint4*>(&lds_k[macro & 1][off]) = live ? stage[i][0] : z;
-            *reinterpret_cast<uint4*>(&lds_v[macro % 3][off]) = live ? stage[i][1] : z;
-        }
+        for (int q = 0; q < 4; ++q)
+            __builtin_amdgcn_global_load_lds(st_pool + next_base + st_lane_off[q],
+                                             (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
+                                             16, 0, 0);
     };
 
     f32x4 acc[EV][CT];
@@ -171,7 +164,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
                     kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                        kt + (32 * sub + 16 * h + i16) * ROW + (4 * kk + g4) * 16));
+                        kt + (32 * sub + 16 * h + i16) * ROW + (((4 * kk + g4) ^ i16) * 16)));
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
                     f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -233,7 +226,14 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             uint32_t vw[8][4];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint4 r = *reinterpret_cast<const uint4*>(vt + (32 * sub + 16 * (j >> 2) + 4 * g4 + (j & 3)) * ROW + i16 * 16);
+                const int k16 = 4 * g4 + (j & 3);                       // key within its 16-key tile
+                const int key = 32 * sub + 16 * (j >> 2) + k16;
+                uint4 r = *reinterpret_cast<const uint4*>(vt + key * ROW + ((i16 ^ k16) * 16));
+                if constexpr (decltype(masked)::value) {
+                    // keys at or beyond the context may hold anything; their probabilities are zero, but a
+                    // NaN would survive the product, so their values are zeroed
+                    if (kMacroKeys * macro + key >= L) r = make_uint4(0u, 0u, 0u, 0u);
+                }
                 vw[j][0] = r.x; vw[j][1] = r.y; vw[j][2] = r.z; vw[j][3] = r.w;
             }
 #pragma unroll
@@ -266,16 +266,15 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const bool late = (wave & 1) != 0;
     // macro steps with a key visible to this wavefront: 0 .. my_macros-1
     const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
-    fetch_bases(0);
-    prefetch();
-    fetch_bases(1);
-    commit(0);
+    fetch_base(0);
+    prefetch(0);
+    fetch_base(1);
     __syncthreads();
     for (int macro = 0; macro < num_macro; ++macro) {
         const bool more = macro + 1 < num_macro;
         if (more) {
-            prefetch();                 // tiles of macro + 1
-            fetch_bases(macro + 2);     // clamped to the request's last tile
+            prefetch(macro + 1);       // lands in the buffers nobody reads during this macro step
+            fetch_base(macro + 2);     // clamped to the request's last tile
         }
         if (!late) {
             if (macro < my_macros) { scores(macro); finish(macro); }
@@ -283,8 +282,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1);
             if (macro < my_macros) scores(macro);
         }
-        if (more) commit(macro + 1);
-        __syncthreads();
+        __syncthreads();               // also waits for this wavefront's tile loads
     }
     if (late && num_macro - 1 < my_macros) finish(num_macro - 1);
 
