@@ -109,11 +109,6 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const int tile_mask = (1 << p.tile_shift) - 1;
     const int64_t page_elems = (static_cast<int64_t>(p.num_kv_heads) * 16 * D) << p.tile_shift;
     const int64_t head_off = (static_cast<int64_t>(kvh) * 16 * D) << p.tile_shift;
-    auto tile_base_of = [&](int u) -> int64_t {   // clamped: never reads a table entry the request does not own
-        const int t = min(u, last_tile);
-        const int pid = __builtin_amdgcn_readfirstlane(bt_row[t >> p.tile_shift]);
-        return static_cast<int64_t>(pid) * page_elems + head_off + (t & tile_mask) * (16 * D);
-    };
 
     // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
     // of 4 KB into LDS.  Wavefront w fetches tile w % TILES of K (w < TILES) or V, one quarter (four
@@ -129,10 +124,18 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         const int key = 4 * q + (lane >> 4);
         st_lane_off[q] = key * D + (((lane & 15) ^ key) * 8);
     }
-    // page ids are fetched (scalar loads) one macro step before the tile loads that need them
-    int64_t next_base;
-    auto fetch_base = [&](int macro) { next_base = tile_base_of(TILES * macro + st_tile); };
-    auto prefetch = [&](int macro) {   // loads of macro step `macro`, whose base was fetched last
+    // The page id of a tile is loaded one macro step before the tile loads that need it and is only
+    // looked at (made wave-uniform) right before them, after the barrier in between has waited for
+    // it anyway: no wait for it of its own.
+    int next_pid, next_in_page;
+    auto fetch_base = [&](int macro) {   // clamped: never reads a table entry the request does not own
+        const int t = min(TILES * macro + st_tile, last_tile);
+        next_pid = bt_row[t >> p.tile_shift];
+        next_in_page = (t & tile_mask) * (16 * D);
+    };
+    auto prefetch = [&](int macro) {   // loads of macro step `macro`, whose page id was fetched last
+        const int64_t next_base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(next_pid)) * page_elems +
+                                  head_off + next_in_page;
         unsigned char* dst = (st_is_v ? lds_v[macro % 3] : lds_k[macro & 1]) + st_tile * 16 * ROW;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
