@@ -12,9 +12,13 @@
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
 //   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
 //     (global_load_lds, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
-//     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
-//     stored XOR-swizzled with the key index (lane l fetches chunk (l % 16) ^ key), which makes
-//     both operand read patterns conflict-free.  One barrier per kMacroKeys keys; the loads of the
+//     LDS contiguously, so rows cannot be padded.  A 16-byte-per-lane LDS read is served 16 lanes
+//     at a time (lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, and the same
+//     in the upper half), and those 16 must hit 16 different chunk positions of the 256-byte bank
+//     row: the K read (lane = key, four chunks per 16 lanes) needs the chunks of a key's row stored
+//     XOR-swizzled with the key index (lane l fetches chunk (l % 16) ^ key); the V read (16 lanes =
+//     the 16 chunks of one key) is conflict-free as stored and a swizzle would break it.
+//     One barrier per kMacroKeys keys; the loads of the
 //     next macro step are in flight during the current one;
 //     half of the wavefronts run their softmax and value phases one macro step late, so that on
 //     every SIMD one wavefront's MFMAs overlap the other's softmax arithmetic;
@@ -112,7 +116,8 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 
     // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
     // of 4 KB into LDS.  Wavefront w fetches tile w % TILES of K (w < TILES) or V, one quarter (four
-    // keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk (l % 16) ^ key. ----
+    // keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk (l % 16) ^ key for K
+    // and chunk l % 16 for V. ----
     constexpr int TILES = kMacroKeys / 16;
     static_assert(kPrefillWaves == 2 * TILES, "one wavefront per staged tile");
     const int st_tile = wave % TILES;
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int key = 4 * q + (lane >> 4);
-        st_lane_off[q] = key * D + (((lane & 15) ^ key) * 8);
+        st_lane_off[q] = key * D + (((lane & 15) ^ (st_is_v ? 0 : key)) * 8);
     }
     // The page id of a tile is loaded one macro step before the tile loads that need it and is only
     // looked at (made wave-uniform) right before them, after the barrier in between has waited for
@@ -133,13 +138,16 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         next_pid = bt_row[t >> p.tile_shift];
         next_in_page = (t & tile_mask) * (16 * D);
     };
-    auto prefetch = [&](int macro) {   // loads of macro step `macro`, whose page id was fetched last
+    auto stage_of = [&](int macro) -> unsigned char* {   // where this wavefront's tile of macro step `macro` goes
+        return (st_is_v ? lds_v[macro % 3] : lds_k[macro & 1]) + st_tile * 16 * ROW;
+    };
+    // loads of the macro step whose page id was fetched last
+    auto prefetch = [&](unsigned char* dst, const uint16_t* pool) __attribute__((always_inline)) {
         const int64_t next_base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(next_pid)) * page_elems +
                                   head_off + next_in_page;
-        unsigned char* dst = (st_is_v ? lds_v[macro % 3] : lds_k[macro & 1]) + st_tile * 16 * ROW;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_global_load_lds(st_pool + next_base + st_lane_off[q],
+            __builtin_amdgcn_global_load_lds(pool + next_base + st_lane_off[q],
                                              (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
                                              16, 0, 0);
     };
@@ -157,8 +165,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // phase are issued back to back: (1) all scores of the kMacroKeys keys, (2) one online-softmax
     // update per column over all of them, (3) the value products.
     f32x4 s[SUB][CT][2];     // scores; lane (i16, g4) holds, for column i16 of tile ct, keys 32*sub + 16*h + 4*g4 + r
-    auto scores = [&](int macro) __attribute__((always_inline)) {
-        const unsigned char* kt = lds_k[macro & 1];
+    auto scores = [&](const unsigned char* kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 }
             }
     };
-    auto softmax_and_values = [&](int macro, auto masked) __attribute__((always_inline)) {
+    auto softmax_and_values = [&](int macro, const unsigned char* vt, auto masked) __attribute__((always_inline)) {
         bf16x8 pb[SUB][CT];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
@@ -223,7 +230,6 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             l[ct] += sum;
         }
         // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4
-        const unsigned char* vt = lds_v[macro % 3];
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub) {
             uint32_t vw[8][4];
@@ -231,7 +237,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             for (int j = 0; j < 8; ++j) {
                 const int k16 = 4 * g4 + (j & 3);                       // key within its 16-key tile
                 const int key = 32 * sub + 16 * (j >> 2) + k16;
-                uint4 r = *reinterpret_cast<const uint4*>(vt + key * ROW + ((i16 ^ k16) * 16));
+                uint4 r = *reinterpret_cast<const uint4*>(vt + key * ROW + i16 * 16);
                 if constexpr (decltype(masked)::value) {
                     // keys at or beyond the context may hold anything; their probabilities are zero, but a
                     // NaN would survive the product, so their values are zeroed
@@ -255,10 +261,10 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     using Plain = std::integral_constant<bool, false>;
     using Masked = std::integral_constant<bool, true>;
     // phases 2 and 3 of macro step `macro`, if any of its keys is visible to this wavefront
-    auto finish = [&](int macro) __attribute__((always_inline)) {
+    auto finish = [&](int macro, const unsigned char* vt) __attribute__((always_inline)) {
         const int first_key = kMacroKeys * macro;
-        if (first_key + kMacroKeys - 1 > pos_min) softmax_and_values(macro, Masked{});
-        else softmax_and_values(macro, Plain{});
+        if (first_key + kMacroKeys - 1 > pos_min) softmax_and_values(macro, vt, Masked{});
+        else softmax_and_values(macro, vt, Plain{});
     };
 
     // ---- main loop: one barrier per macro step.  The two wavefronts that share a SIMD (w and
@@ -266,28 +272,39 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // MFMAs) while the early half computes the scores of macro step M (MFMAs, then its softmax), so
     // that one's VALU phase overlaps the other's MFMA phases.  That is why V has a third LDS buffer.
     const int num_macro = (num_steps + SUB - 1) / SUB;
+#ifdef OSERVE_PF_LATE_HI
+    const bool late = wave >= kPrefillWaves / 2;
+#else
     const bool late = (wave & 1) != 0;
+#endif
     // macro steps with a key visible to this wavefront: 0 .. my_macros-1
     const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
-    fetch_base(0);
-    prefetch(0);
-    fetch_base(1);
-    __syncthreads();
-    for (int macro = 0; macro < num_macro; ++macro) {
-        const bool more = macro + 1 < num_macro;
-        if (more) {
-            prefetch(macro + 1);       // lands in the buffers nobody reads during this macro step
+    // One macro step.  The tile loads it issues land in buffers that nobody reads before the next
+    // barrier; the pointers are declared non-overlapping so that the LDS reads of this step are not
+    // made to wait for those loads.
+    auto step = [&](int macro, unsigned char* __restrict__ dst, const uint16_t* __restrict__ pool,
+                    const unsigned char* __restrict__ kt, const unsigned char* __restrict__ vt)
+                    __attribute__((always_inline)) {
+        if (macro + 1 < num_macro) {
+            prefetch(dst, pool);
             fetch_base(macro + 2);     // clamped to the request's last tile
         }
         if (!late) {
-            if (macro < my_macros) { scores(macro); finish(macro); }
+            if (macro < my_macros) { scores(kt); finish(macro, vt); }
         } else {
-            if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1);
-            if (macro < my_macros) scores(macro);
+            if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1, vt);
+            if (macro < my_macros) scores(kt);
         }
+    };
+    fetch_base(0);
+    prefetch(stage_of(0), st_pool);
+    fetch_base(1);
+    __syncthreads();
+    for (int macro = 0; macro < num_macro; ++macro) {
+        step(macro, stage_of(macro + 1), st_pool, lds_k[macro & 1], lds_v[(macro + (late ? 2 : 0)) % 3]);
         __syncthreads();               // also waits for this wavefront's tile loads
     }
-    if (late && num_macro - 1 < my_macros) finish(num_macro - 1);
+    if (late && num_macro - 1 < my_macros) finish(num_macro - 1, lds_v[(num_macro - 1) % 3]);
 
     // ---- write out: lane holds column i16 of each tile, dims 8*(4*g4 + r) + e ----
 #pragma unroll
