@@ -12,12 +12,12 @@
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
 //   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
 //     (global_load_lds, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
-//     LDS contiguously, so rows cannot be padded.  A 16-byte-per-lane LDS read is served 16 lanes
-//     at a time (lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, and the same
-//     in the upper half), and those 16 must hit 16 different chunk positions of the 256-byte bank
-//     row: the K read (lane = key, four chunks per 16 lanes) needs the chunks of a key's row stored
-//     XOR-swizzled with the key index (lane l fetches chunk (l % 16) ^ key); the V read (16 lanes =
-//     the 16 chunks of one key) is conflict-free as stored and a swizzle would break it.
+//     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
+//     stored XOR-swizzled.  A 16-byte-per-lane LDS read is served 16 lanes at a time (measured:
+//     lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, the same in the upper
+//     half), and those 16 must hit 16 different chunk positions of the 256-byte bank row: K chunks
+//     are XOR-ed with the key index (lane l fetches chunk (l % 16) ^ key).  V is read with the
+//     transposing 8-byte read, 32 lanes served together: V chunks are XOR-ed with 2 (key % 8).
 //     One barrier per kMacroKeys keys; the loads of the
 //     next macro step are in flight during the current one;
 //     half of the wavefronts run their softmax and value phases one macro step late, so that on
@@ -30,7 +30,7 @@
 //     wavefront's diagonal;
 //   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
 //     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
-//     and V^T is assembled to match with byte permutes.
+//     and the transposing LDS read (ds_read_b64_tr_b16) delivers V^T in exactly that order.
 // Accumulation is fp32; P is rounded to bf16 for the second product.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
@@ -47,6 +47,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
@@ -127,7 +128,18 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int key = 4 * q + (lane >> 4);
-        st_lane_off[q] = key * D + (((lane & 15) ^ (st_is_v ? 0 : key)) * 8);
+        st_lane_off[q] = key * D + (((lane & 15) ^ (st_is_v ? 2 * (key & 7) : key)) * 8);
+    }
+    // V is read back with the transposing 8-byte LDS read: in each group of 16 lanes, lane s supplies
+    // the address of four consecutive dims (4 (s % 4) ..) of key 4 g4 + s / 4, and lane i receives dim i
+    // of the four keys.  The 16-byte chunks of a V row are stored XOR-ed with 2 (key % 8), which spreads
+    // the 32 lanes served together over all banks.
+    int v_off[EV];
+    {
+        const int key = 4 * g4 + (i16 >> 2);
+        const int t = ((i16 & 3) >> 1) ^ (2 * (key & 7));
+#pragma unroll
+        for (int e = 0; e < EV; ++e) v_off[e] = key * ROW + ((2 * e) ^ t) * 16 + (i16 & 1) * 8;
     }
     // The page id of a tile is loaded one macro step before the tile loads that need it and is only
     // looked at (made wave-uniform) right before them, after the barrier in between has waited for
@@ -229,29 +241,28 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
             }
             l[ct] += sum;
         }
-        // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4
+        // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4.  One
+        // transposing read hands lane (i16, g4) the values of dim 16*e + i16 at keys 4*g4 .. 4*g4+3 of
+        // one 16-key half: half of the A operand of tile e, no permutes.
 #pragma unroll
         for (int sub = 0; sub < SUB; ++sub) {
-            uint32_t vw[8][4];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k16 = 4 * g4 + (j & 3);                       // key within its 16-key tile
-                const int key = 32 * sub + 16 * (j >> 2) + k16;
-                uint4 r = *reinterpret_cast<const uint4*>(vt + key * ROW + i16 * 16);
-                if constexpr (decltype(masked)::value) {
-                    // keys at or beyond the context may hold anything; their probabilities are zero, but a
-                    // NaN would survive the product, so their values are zeroed
-                    if (kMacroKeys * macro + key >= L) r = make_uint4(0u, 0u, 0u, 0u);
-                }
-                vw[j][0] = r.x; vw[j][1] = r.y; vw[j][2] = r.z; vw[j][3] = r.w;
-            }
 #pragma unroll
             for (int e = 0; e < EV; ++e) {
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                uint32_t a[4];
+                s16x4 half[2];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) a[j] = __builtin_amdgcn_perm(vw[2 * j + 1][e >> 1], vw[2 * j][e >> 1], sel);
-                const bf16x8 av = __builtin_bit_cast(bf16x8, make_uint4(a[0], a[1], a[2], a[3]));
+                for (int h = 0; h < 2; ++h) {
+                    half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4*)(vt + (32 * sub + 16 * h) * ROW + v_off[e]));
+                    if constexpr (decltype(masked)::value) {
+                        // keys at or beyond the context may hold anything; their probabilities are zero, but a
+                        // NaN would survive the product, so their values are zeroed
+                        const int key0 = kMacroKeys * macro + 32 * sub + 16 * h + 4 * g4;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (key0 + r >= L) half[h][r] = 0;
+                    }
+                }
+                const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[sub][ct], acc[e][ct], 0, 0, 0);
@@ -306,7 +317,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     }
     if (late && num_macro - 1 < my_macros) finish(num_macro - 1, lds_v[(num_macro - 1) % 3]);
 
-    // ---- write out: lane holds column i16 of each tile, dims 8*(4*g4 + r) + e ----
+    // ---- write out: lane holds column i16 of each tile, dims 16*e + 4*g4 + r ----
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         float l_tot = l[ct] + xor_f32(l[ct], 16);
@@ -314,19 +325,17 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         const int c = 16 * ct + i16;
         if (tok[ct] < n) {
             const int head = kvh * p.group + (c & (p.group - 1));
-            float* dst = p.out + (static_cast<int64_t>(q_row0 + tok[ct]) * p.num_q_heads + head) * D + 4 * EV * g4;
+            float* dst = p.out + (static_cast<int64_t>(q_row0 + tok[ct]) * p.num_q_heads + head) * D + 4 * g4;
             const float inv = 1.f / l_tot;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int e4 = 0; e4 < EV / 4; ++e4) {
-                    float4 o;
-                    o.x = acc[4 * e4 + 0][ct][r] * inv;
-                    o.y = acc[4 * e4 + 1][ct][r] * inv;
-                    o.z = acc[4 * e4 + 2][ct][r] * inv;
-                    o.w = acc[4 * e4 + 3][ct][r] * inv;
-                    *reinterpret_cast<float4*>(dst + r * EV + 4 * e4) = o;
-                }
+            for (int e = 0; e < EV; ++e) {
+                float4 o;
+                o.x = acc[e][ct][0] * inv;
+                o.y = acc[e][ct][1] * inv;
+                o.z = acc[e][ct][2] * inv;
+                o.w = acc[e][ct][3] * inv;
+                *reinterpret_cast<float4*>(dst + 16 * e) = o;
+            }
         }
     }
 }
