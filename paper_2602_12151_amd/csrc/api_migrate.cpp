@@ -17,7 +17,7 @@ struct oserve_kv_migration {
     int32_t max_request_pages = 0;
     int64_t num_pages = 0;
     std::vector<int32_t> offsets;   // [R + 1]
-    int32_t* dev = nullptr;         // [R] source table rows, then [R + 1] offsets
+    int32_t* dev = nullptr;         // [num_pages][4]: source table row, request, page within the request, 0
     hipEvent_t t_begin = nullptr, t_end = nullptr;
     bool timing = false, t_pending = false;
     double t_sum_ms = 0.0;
@@ -70,9 +70,8 @@ oserve_status_t run(oserve_kv_migration* m, bool gather, const void* k_src, cons
     p.k_src = k_src; p.v_src = v_src; p.k_dst = k_dst; p.v_dst = v_dst;
     p.block_table = table;
     p.table_stride = table_stride;
-    p.table_rows = use_rows ? m->dev : nullptr;
-    p.page_offsets = m->dev + m->num_requests;
-    p.num_requests = m->num_requests;
+    p.page_refs = m->dev;
+    p.use_source_rows = use_rows ? 1 : 0;
     p.num_pages = m->num_pages;
     p.pool_heads = pool_heads;
     p.head_begin = head_begin;
@@ -121,11 +120,16 @@ oserve_status_t oserve_kv_migration_create(const int32_t* context_lens_host, con
         if (ok) {
             Guard guard(device_id);
             ok = guard.ok;
-            const size_t bytes = (2 * static_cast<size_t>(num_requests) + 1) * sizeof(int32_t);
+            // per staging page, which table entry names it: the copy kernel starts from one load
+            std::vector<int32_t> refs(4 * static_cast<size_t>(total));
+            for (int32_t r = 0; r < num_requests; ++r)
+                for (int32_t s = m->offsets[r]; s < m->offsets[r + 1]; ++s) {
+                    int32_t* e = &refs[4 * static_cast<size_t>(s)];
+                    e[0] = table_rows_host[r]; e[1] = r; e[2] = s - m->offsets[r]; e[3] = 0;
+                }
+            const size_t bytes = refs.size() * sizeof(int32_t);
             ok = ok && hipMalloc(reinterpret_cast<void**>(&m->dev), bytes) == hipSuccess;
-            ok = ok && hipMemcpy(m->dev, table_rows_host, sizeof(int32_t) * num_requests, hipMemcpyHostToDevice) == hipSuccess;
-            ok = ok && hipMemcpy(m->dev + num_requests, m->offsets.data(), sizeof(int32_t) * (num_requests + 1),
-                                 hipMemcpyHostToDevice) == hipSuccess;
+            ok = ok && hipMemcpy(m->dev, refs.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
             ok = ok && hipEventCreate(&m->t_begin) == hipSuccess && hipEventCreate(&m->t_end) == hipSuccess;
         }
         if (!ok) { release(m); delete m; return OSERVE_ERR_DEVICE; }

@@ -101,10 +101,10 @@ struct MigrateParams {
     void* v_dst;
     const int32_t* block_table;   // names the pool pages (source table for gather, target table for scatter)
     int32_t table_stride;         // entries per table row
-    const int32_t* table_rows;    // [num_requests] row of each migrating request, or null: row r
-    const int32_t* page_offsets;  // [num_requests + 1] first staging page of each request
-    int32_t num_requests;
-    int64_t num_pages;            // staging pages = page_offsets[num_requests]
+    const int32_t* page_refs;     // [num_pages][4] per staging page: source table row of its request, index of its
+                                  // request, page index within the request, 0
+    int32_t use_source_rows;      // table row of a page: its request's source row (1) or its request's index (0)
+    int64_t num_pages;            // staging pages
     int32_t pool_heads;           // kv heads per page in the pool
     int32_t head_begin;           // first pool head of the copied range
     int32_t num_heads;            // heads copied (= heads per page of the staging chunk)

@@ -30,20 +30,15 @@ __global__ __launch_bounds__(kMigrateThreads) void kv_migrate_kernel(const Migra
     // the copied heads of one page are contiguous both in the pool and in the staging chunk
     const int page_chunks = p.num_heads * p.unit_chunks;
     for (int64_t s = blockIdx.x; s < p.num_pages; s += gridDim.x) {
-        // request of staging page s: last r with offsets[r] <= s
-        int lo = 0, hi = p.num_requests;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (static_cast<int64_t>(p.page_offsets[mid]) <= s) lo = mid; else hi = mid;
-        }
-        const int row = p.table_rows ? p.table_rows[lo] : lo;
-        const int pid = __builtin_amdgcn_readfirstlane(
-            p.block_table[static_cast<int64_t>(row) * p.table_stride + static_cast<int>(s - p.page_offsets[lo])]);
+        // which table entry names the page: one 16-byte wave-uniform load
+        const int4 ref = reinterpret_cast<const int4*>(p.page_refs)[s];
+        const int row = p.use_source_rows ? ref.x : ref.y;
+        const int pid = __builtin_amdgcn_readfirstlane(p.block_table[static_cast<int64_t>(row) * p.table_stride + ref.z]);
         const int64_t pool_off = (static_cast<int64_t>(pid) * p.pool_heads + p.head_begin) * p.unit_chunks;
         const int64_t stage_off = s * page_chunks;
         const u32x4* from = pool_or_stage_src + (GATHER ? pool_off : stage_off);
         u32x4* to = dst + (GATHER ? stage_off : pool_off);
-        constexpr int U = 4;   // 16-byte loads in flight per thread
+        constexpr int U = 8;   // 16-byte loads in flight per thread: a 32 KB page in one round
         int c = threadIdx.x;
         for (; c + (U - 1) * kMigrateThreads < page_chunks; c += U * kMigrateThreads) {
             u32x4 w[U];
@@ -61,8 +56,11 @@ __global__ __launch_bounds__(kMigrateThreads) void kv_migrate_kernel(const Migra
 hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, int num_cus, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop) {
     if (p.num_pages <= 0) return hipSuccess;
-    // enough resident workgroups to fill the device, each striding over the pages
-    const int64_t cap = static_cast<int64_t>(num_cus) * 16;
+    // one workgroup per page and pool (measured: a short-lived workgroup per 8-32 KB span copies
+    // faster than resident workgroups striding over the pages); the stride loop only serves
+    // chunks beyond the grid limit
+    (void)num_cus;
+    const int64_t cap = int64_t{1} << 30;
     const dim3 grid(static_cast<unsigned>(p.num_pages < cap ? p.num_pages : cap), 2);
     if (gather)
         hipExtLaunchKernelGGL((kv_migrate_kernel<true>), grid, dim3(kMigrateThreads), 0, stream, start, stop, 0, p);

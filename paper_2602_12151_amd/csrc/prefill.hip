@@ -283,11 +283,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     // MFMAs) while the early half computes the scores of macro step M (MFMAs, then its softmax), so
     // that one's VALU phase overlaps the other's MFMA phases.  That is why V has a third LDS buffer.
     const int num_macro = (num_steps + SUB - 1) / SUB;
-#ifdef OSERVE_PF_LATE_HI
     const bool late = wave >= kPrefillWaves / 2;
-#else
-    const bool late = (wave & 1) != 0;
-#endif
     // macro steps with a key visible to this wavefront: 0 .. my_macros-1
     const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
     // One macro step.  The tile loads it issues land in buffers that nobody reads before the next
