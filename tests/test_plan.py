@@ -179,8 +179,10 @@ def test_prefill_plan_items_cover_every_query_block_once():
             assert key not in seen
             seen.add(key)
             lane_of_group.setdefault((b, it["kv_head"]), set()).add(i % 8)
-        # while all eight lists still have items, the blocks of a (request, kv head) share the index modulo 8
+        # while all eight lists still have items, the blocks of a (request, kv head) share the index modulo 8;
+        # with fewer than eight (request, kv head) pairs their blocks have to spread over the XCDs instead
         big = [g for g, lanes in lane_of_group.items() if qlens[g[0]] > qb]
-        assert any(len(lane_of_group[g]) == 1 for g in big) or not big
+        if len(lane_of_group) >= 8:
+            assert any(len(lane_of_group[g]) == 1 for g in big) or not big
         assert len(seen) == sum(-(-n // qb) for n in qlens) * hkv
         assert plan.query_tokens == sum(qlens)
