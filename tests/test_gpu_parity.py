@@ -274,3 +274,19 @@ def test_rerun_bit_identical_at_full_size():
     again = op.step(dev).clone()
     torch.cuda.synchronize()
     assert torch.equal(out, again)
+
+
+def test_one_request_of_a_million_tokens():
+    """Batch 1, 1,048,583 tokens (65,537 pages, ragged last page): the largest context the planner's bounds are
+    sized for, compared on sampled heads; every other batch shape splits less."""
+    L = (1 << 20) + 7
+    w = wl.Workload(11, "one very long request", batch=1, num_q_heads=32, num_kv_heads=8, head_dim=128)
+    dev = wl.make_inputs(w, device="cuda", seed=11, lens=np.array([L], dtype=np.int32))
+    out, op = gh.gpu_attention(dev)
+    assert torch.isfinite(out).all()
+    pairs = [(0, 0), (0, 13), (0, 31)]
+    ref = gh.sampled_oracle_rows(dev, pairs)
+    got = torch.stack([out[b, h] for b, h in pairs])
+    err = gh.assert_parity(got, ref, "one request of 2^20 + 7 tokens")
+    print(f"2^20+7 tokens: items {op.plan.num_work_items}, split pages {op.plan.split_pages}, "
+          f"max_abs {err[0]:.2e}, rel_l2 {err[1]:.2e}")

@@ -113,3 +113,60 @@ def test_plan_errors():
     with pytest.raises(binding.OserveError) as e:
         plan.update([100], [17])
     assert e.value.status == binding.ERR_PLAN_MISMATCH
+
+
+def _oracle_row(inp, q, row, h, b, visible, group):
+    """Oracle output of query row `row`, head h, of request b, which sees the first `visible` cached tokens:
+    a decode step over that prefix (only the needed pages of one kv head are copied to the host)."""
+    ps = inp.workload.page_size
+    n = (visible + ps - 1) // ps
+    ids = inp.block_table[b, :n].long()
+    j = h // group
+    k = inp.k_pages[ids, j:j + 1].cpu()
+    v = inp.v_pages[ids, j:j + 1].cpu()
+    bt = np.arange(n, dtype=np.int32)[None, :]
+    return oracle.paged_decode_attn(q[row:row + 1, h:h + 1].cpu(), k, v, bt, np.array([visible], dtype=np.int32),
+                                    inp.scale)[0, 0]
+
+
+@pytest.mark.parametrize("which", [1, 2])
+def test_bench_workloads_sampled(which):
+    """The workloads `bench.py --prefill 1|2` times, at full size and in its launch configuration, against the
+    oracle on sampled (query token, head) rows: first and last token of a chunk, both sides of block
+    boundaries, random ones."""
+    if which == 1:
+        lens, qlens = np.full(8, 32768), np.full(8, 2048)
+    else:
+        lens, qlens = wl.CounterRng(20260212 + 102).integers(8192, 32768, 64), np.full(64, 512)
+    lens, qlens = lens.astype(np.int32), qlens.astype(np.int32)
+    w = wl.Workload(100 + which, "prefill", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 1)
+    q = torch.randn(int(qlens.sum()), 32, 128, generator=gen, device="cuda").to(torch.bfloat16)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    plan = binding.PrefillPlan(lens, qlens, 32, 8, 128, 16, inp.block_table.shape[1], 0)
+    binding.paged_prefill_attn(plan, q, inp.k_pages, inp.v_pages, inp.block_table, w.scale, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    rng = np.random.default_rng(77 + which)
+    row0 = np.concatenate([[0], np.cumsum(qlens)])
+    picks = []
+    for b in (0, len(lens) - 1, int(np.argmax(lens))):
+        n = int(qlens[b])
+        for i in (0, 1, 63, 64, 65, n // 2, n - 2, n - 1):
+            picks.append((b, i, int(rng.integers(0, 32))))
+    for _ in range(24):
+        b = int(rng.integers(0, len(lens)))
+        picks.append((b, int(rng.integers(0, qlens[b])), int(rng.integers(0, 32))))
+    got, ref = [], []
+    for b, i, h in picks:
+        row = int(row0[b]) + i
+        got.append(out[row, h])
+        ref.append(_oracle_row(inp, q, row, h, b, int(lens[b] - qlens[b]) + i + 1, w.group))
+    got, ref = torch.stack(got), np.stack(ref)
+    err = gh.assert_parity(got, ref, f"prefill bench workload {which}")
+    per_row = np.linalg.norm(got.cpu().double().numpy() - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert per_row.max() <= 2 * gh.REL_L2_TOL, per_row.max()
+    print(f"prefill bench workload {which}: {len(picks)} rows, max_abs {err[0]:.2e}, rel_l2 {err[1]:.2e}, "
+          f"worst row {per_row.max():.2e}")
