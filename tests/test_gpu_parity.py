@@ -99,7 +99,10 @@ def test_page_sizes_32_and_64(page_size, hq, hkv, d):
 
 @pytest.mark.parametrize("name,hq,hkv", [("OPT-30B (MHA, 56 heads) TP=2", 28, 28), ("OPT-66B (MHA, 72 heads) TP=4", 18, 18),
                                          ("Llama-30B (MHA, 52 heads) TP=4", 13, 13), ("Llama2-70B TP=2", 32, 4),
-                                         ("Llama2-70B TP=8", 8, 1), ("Llama2-70B TP=1", 64, 8)])
+                                         ("Llama2-70B TP=8", 8, 1), ("Llama2-70B TP=1", 64, 8),
+                                         ("Llama2-70B TP=3, GPU holding 3 of the 8 kv heads", 24, 3),
+                                         ("Llama2-70B TP=3, GPU holding 2 of the 8 kv heads", 16, 2),
+                                         ("OPT-30B (56 heads) TP=3, GPU holding 19 heads", 19, 19)])
 def test_head_geometries_of_the_papers_models(name, hq, hkv):
     """Per-GPU head counts of the models of section 6.1 at tensor-parallel degrees its deployments use
     (all head_dim 128), on a small mixed-length batch."""
