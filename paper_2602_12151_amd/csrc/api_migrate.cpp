@@ -11,7 +11,6 @@
 
 struct oserve_kv_migration {
     int32_t device_id = -1;
-    int32_t num_cus = 256;
     int32_t num_requests = 0;
     int32_t page_size = 0;
     int32_t max_request_pages = 0;
@@ -77,7 +76,7 @@ oserve_status_t run(oserve_kv_migration* m, bool gather, const void* k_src, cons
     p.head_begin = head_begin;
     p.num_heads = num_heads;
     p.unit_chunks = m->page_size * head_dim * 2 / 16;
-    if (oserve::launch_kv_migrate(p, gather, m->num_cus, static_cast<hipStream_t>(stream_v),
+    if (oserve::launch_kv_migrate(p, gather, static_cast<hipStream_t>(stream_v),
                                   m->timing ? m->t_begin : nullptr, m->timing ? m->t_end : nullptr) != hipSuccess)
         return OSERVE_ERR_DEVICE;
     if (m->timing) m->t_pending = true;
@@ -114,9 +113,8 @@ oserve_status_t oserve_kv_migration_create(const int32_t* context_lens_host, con
     m->offsets[num_requests] = static_cast<int32_t>(total);
     m->num_pages = total;
     if (device_id >= 0) {
-        int n_dev = 0, cus = 0;
+        int n_dev = 0;
         bool ok = hipGetDeviceCount(&n_dev) == hipSuccess && device_id < n_dev;
-        ok = ok && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device_id) == hipSuccess;
         if (ok) {
             Guard guard(device_id);
             ok = guard.ok;
@@ -133,7 +131,6 @@ oserve_status_t oserve_kv_migration_create(const int32_t* context_lens_host, con
             ok = ok && hipEventCreate(&m->t_begin) == hipSuccess && hipEventCreate(&m->t_end) == hipSuccess;
         }
         if (!ok) { release(m); delete m; return OSERVE_ERR_DEVICE; }
-        if (cus > 0) m->num_cus = cus;
     }
     *out = m;
     return OSERVE_OK;

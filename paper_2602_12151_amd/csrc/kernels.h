@@ -52,18 +52,9 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
 // ---- chunked prefill (prefill.hip) ----
-#ifndef OSERVE_PF_WAVES
-#define OSERVE_PF_WAVES 8
-#endif
-#ifndef OSERVE_PF_MACRO
-#define OSERVE_PF_MACRO 64
-#endif
-constexpr int kPrefillWaves = OSERVE_PF_WAVES;    // wavefronts per workgroup
-#ifndef OSERVE_PF_CT
-#define OSERVE_PF_CT 2
-#endif
-constexpr int kPrefillColTiles = OSERVE_PF_CT;    // 16-column score tiles per wavefront
-constexpr int kPrefillMacroKeys = OSERVE_PF_MACRO;  // keys staged in LDS per barrier
+constexpr int kPrefillWaves = 8;        // wavefronts per workgroup (two per SIMD)
+constexpr int kPrefillColTiles = 2;     // 16-column score tiles per wavefront
+constexpr int kPrefillMacroKeys = 64;   // keys staged in LDS per barrier
 // query tokens of one work item for a GQA group of 1 << group_shift heads
 inline int prefill_block_tokens(int group_shift) { return kPrefillWaves * ((16 * kPrefillColTiles) >> group_shift); }
 
@@ -111,7 +102,7 @@ struct MigrateParams {
     int32_t unit_chunks;          // 16-byte chunks per (page, head): page_size * head_dim * 2 / 16
 };
 
-hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, int num_cus, hipStream_t stream,
+hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop);
 
 }  // namespace oserve

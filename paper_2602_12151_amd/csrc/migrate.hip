@@ -53,13 +53,12 @@ __global__ __launch_bounds__(kMigrateThreads) void kv_migrate_kernel(const Migra
 
 }  // namespace
 
-hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, int num_cus, hipStream_t stream,
+hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop) {
     if (p.num_pages <= 0) return hipSuccess;
     // one workgroup per page and pool (measured: a short-lived workgroup per 8-32 KB span copies
     // faster than resident workgroups striding over the pages); the stride loop only serves
     // chunks beyond the grid limit
-    (void)num_cus;
     const int64_t cap = int64_t{1} << 30;
     const dim3 grid(static_cast<unsigned>(p.num_pages < cap ? p.num_pages : cap), 2);
     if (gather)
