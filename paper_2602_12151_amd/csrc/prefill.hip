@@ -124,11 +124,11 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     const int st_tile = wave % TILES;
     const bool st_is_v = wave >= TILES;
     const uint16_t* st_pool = st_is_v ? p.v_pages : p.k_pages;
-    int st_lane_off[4];                    // element offset of this lane's chunk within the tile, per quarter
+    int st_lane_off[4];                    // byte offset of this lane's chunk within the tile, per quarter
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int key = 4 * q + (lane >> 4);
-        st_lane_off[q] = key * D + (((lane & 15) ^ (st_is_v ? 2 * (key & 7) : key)) * 8);
+        st_lane_off[q] = (key * D + (((lane & 15) ^ (st_is_v ? 2 * (key & 7) : key)) * 8)) * 2;
     }
     // V is read back with the transposing 8-byte LDS read: in each group of 16 lanes, lane s supplies
     // the address of four consecutive dims (4 (s % 4) ..) of key 4 g4 + s / 4, and lane i receives dim i
@@ -157,11 +157,19 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
     auto prefetch = [&](unsigned char* dst, const uint16_t* pool) __attribute__((always_inline)) {
         const int64_t next_base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(next_pid)) * page_elems +
                                   head_off + next_in_page;
+        // The tile is addressed through a buffer descriptor of its own (base = the tile, 4 KB long): a
+        // buffer load into LDS counts only in the vector-memory counter, whereas the compiler treats a
+        // global load into LDS as outstanding in the LDS counter as well and then makes every wait for
+        // an LDS read a wait for all of them.
+        const uintptr_t tile = reinterpret_cast<uintptr_t>(pool + next_base);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(tile));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(tile >> 32));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            reinterpret_cast<void*>((static_cast<uintptr_t>(hi) << 32) | lo), 0, 16 * ROW, 0x00020000);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_global_load_lds(pool + next_base + st_lane_off[q],
-                                             (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
-                                             16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
+                                                     16, st_lane_off[q], 0, 0, 0);
     };
 
     f32x4 acc[EV][CT];
@@ -195,6 +203,15 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                     s[sub][ct][h] = a;
                 }
             }
+        // order of this block's K reads and MFMAs: the fragments of two 16-key halves in flight, then
+        // per half its MFMAs followed by the reads of the half after the next
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * KK, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * SUB - 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, CT * KK, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, KK, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * CT * KK, 0);
     };
     auto softmax_and_values = [&](int macro, const unsigned char* vt, auto masked) __attribute__((always_inline)) {
         bf16x8 pb[SUB][CT];
@@ -267,6 +284,19 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                 for (int ct = 0; ct < CT; ++ct)
                     acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[sub][ct], acc[e][ct], 0, 0, 0);
             }
+        }
+        if constexpr (!decltype(masked)::value) {
+            // Order of this block's LDS reads and MFMAs: kAhead reads in flight, then two MFMAs (one row
+            // tile, both column tiles) per two reads, so that a read is waited for only after the MFMAs
+            // of several earlier tiles have been issued, not right after its own issue.
+            constexpr int kReads = 2 * EV * SUB, kAhead = 8;
+            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+            for (int i = 0; i < (kReads - kAhead) / 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, CT, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, CT * kAhead / 2, 0);
         }
     };
     using Plain = std::integral_constant<bool, false>;
