@@ -11,7 +11,7 @@
 // wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
 // workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
 //   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
-//     (global_load_lds, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
+//     (buffer loads with the LDS flag, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
 //     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
 //     stored XOR-swizzled.  A 16-byte-per-lane LDS read is served 16 lanes at a time (measured:
 //     lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, the same in the upper
