@@ -102,23 +102,11 @@ def cpu_baseline(inp, wl, torch, budget_token_heads):
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 peak
 
-PREFILL_WORKLOADS = {
-    0: ("16 whole prompts of 4096 tokens", lambda: (np.full(16, 4096), np.full(16, 4096))),
-    1: ("8 chunks of 2048 tokens ending 32768-token contexts", lambda: (np.full(8, 32768), np.full(8, 2048))),
-    2: ("64 chunks of 512 tokens ending contexts uniform in [8192, 32768]", None),
-}
-
 
 def bench_prefill(args, torch, binding, wl):
     """One step = oserve_prefill_plan_update + the prefill kernel on inputs resident in HBM."""
-    name, make = PREFILL_WORKLOADS[args.prefill]
-    if make is None:
-        lens = wl.CounterRng(20260212 + 100 + args.prefill).integers(8192, 32768, 64)
-        qlens = np.full(64, 512)
-    else:
-        lens, qlens = make()
-    lens, qlens = lens.astype(np.int32), qlens.astype(np.int32)
-    w = wl.Workload(100 + args.prefill, "prefill", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    name = wl.PREFILL_WORKLOAD_NAMES[args.prefill]
+    w, lens, qlens = wl.prefill_workload(args.prefill)
     inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed + 1)

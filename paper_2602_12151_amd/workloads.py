@@ -162,6 +162,28 @@ def context_lens(w: Workload, seed: Optional[int] = None) -> np.ndarray:
     return lens.astype(np.int32)
 
 
+PREFILL_WORKLOAD_NAMES = (
+    "16 whole prompts of 4096 tokens",
+    "8 chunks of 2048 tokens ending 32768-token contexts",
+    "64 chunks of 512 tokens ending contexts uniform in [8192, 32768]",
+)
+
+
+def prefill_workload(which: int):
+    """(Workload, context lengths, query lengths) of chunked-prefill workload `which` (Llama-3-8B heads):
+    request b brings the last qlens[b] of its lens[b] cached tokens as query tokens."""
+    if which == 0:
+        lens, qlens = np.full(16, 4096), np.full(16, 4096)
+    elif which == 1:
+        lens, qlens = np.full(8, 32768), np.full(8, 2048)
+    elif which == 2:
+        lens, qlens = CounterRng(20260212 + 100 + which).integers(8192, 32768, 64), np.full(64, 512)
+    else:
+        raise ValueError(f"unknown prefill workload {which}")
+    w = Workload(100 + which, "prefill", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    return w, lens.astype(np.int32), qlens.astype(np.int32)
+
+
 def pages_needed(lens: np.ndarray, page_size: int = PAGE_SIZE) -> np.ndarray:
     return (lens.astype(np.int64) + page_size - 1) // page_size
 

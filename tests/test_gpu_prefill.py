@@ -129,17 +129,12 @@ def _oracle_row(inp, q, row, h, b, visible, group):
                                     inp.scale)[0, 0]
 
 
-@pytest.mark.parametrize("which", [1, 2])
+@pytest.mark.parametrize("which", [0, 1, 2])
 def test_bench_workloads_sampled(which):
-    """The workloads `bench.py --prefill 1|2` times, at full size and in its launch configuration, against the
+    """The workloads `bench.py --prefill 0|1|2` times, at full size and in its launch configuration, against the
     oracle on sampled (query token, head) rows: first and last token of a chunk, both sides of block
     boundaries, random ones."""
-    if which == 1:
-        lens, qlens = np.full(8, 32768), np.full(8, 2048)
-    else:
-        lens, qlens = wl.CounterRng(20260212 + 102).integers(8192, 32768, 64), np.full(64, 512)
-    lens, qlens = lens.astype(np.int32), qlens.astype(np.int32)
-    w = wl.Workload(100 + which, "prefill", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    w, lens, qlens = wl.prefill_workload(which)
     inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed + 1)
