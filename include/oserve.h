@@ -269,8 +269,9 @@ oserve_status_t oserve_prefill_plan_kernel_ms(oserve_prefill_plan_t* plan, float
 typedef struct oserve_kv_migration oserve_kv_migration_t;
 
 /*
- * The migrating requests.  Host-only except for a small device copy of the two
- * index arrays, allocated here and owned by the object (this call synchronises).
+ * The migrating requests.  Host-only except for one device array of 16 bytes per
+ * staging page (which table entry names the page), allocated here and owned by
+ * the object (this call synchronises).
  *   context_lens_host  [num_requests] int32 host: L_r >= 1
  *   table_rows_host    [num_requests] int32 host: row of request r in the SOURCE block table
  *   device_id          -1 = host object only (cannot launch)
