@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the split kernel (read + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # scaled by a plain copy of known size: profiles/split_kernel_cfg3_heterogeneous_mix.md.  Only the
 # workload that was profiled has an entry; the others report null.
-MEASURED_TRAFFIC_BYTES = {3: 6_959_823_667 + 10_751_590}
+MEASURED_TRAFFIC_BYTES = {3: 3_397_209 * 2048 + 10_499 * 1024}
 
 
 def parse_args():
