@@ -55,6 +55,7 @@ constexpr int kPrefillThreads = 64 * kPrefillWaves;
 constexpr int kColTiles = kPrefillColTiles;
 constexpr int kStepKeys = 32;
 constexpr int kMacroKeys = kPrefillMacroKeys;
+constexpr float kRescaleSlack = 8.f;   // log2 units: weights up to 256 before the reference maximum moves
 
 template <int D>
 __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4))) void paged_prefill_kernel(const PrefillParams p) {
@@ -232,7 +233,12 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
                     }
             // m is kept in scaled (log2) units; the scale is positive, so raw scores order like scaled ones
             mx *= p.scale_log2e;
-            if (__builtin_amdgcn_ballot_w64(mx > m[ct]) != 0) {
+            // The running maximum is only a reference point: the result does not depend on it as long as
+            // nothing overflows, so it is moved (and the accumulators rescaled) only when some score
+            // exceeds it by more than kRescaleSlack, i.e. the weights stay below 2^kRescaleSlack.  On
+            // the first steps of a prompt the true maximum rises at almost every step; its small
+            // increments are not worth 64 multiplications and two cross-lane exchanges each.
+            if (__builtin_amdgcn_ballot_w64(mx > m[ct] + kRescaleSlack) != 0) {
                 mx = fmaxf(mx, xor_f32(mx, 16));
                 mx = fmaxf(mx, xor_f32(mx, 32));
                 const float m_new = fmaxf(m[ct], mx);
