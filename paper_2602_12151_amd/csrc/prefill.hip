@@ -25,9 +25,9 @@
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
 //   * online softmax in the log2 domain, one update per column and macro step, per-column state
-//     lane-local, maxima exchanged across lanes only when some lane's keys beat the running
-//     maximum; the causal mask is a select and is applied only on the macro steps that straddle a
-//     wavefront's diagonal;
+//     lane-local; the running maximum is a reference point that moves (maxima exchanged across
+//     lanes, accumulators rescaled) only when some score exceeds it by 8 log2 units; the causal
+//     mask is a select and is applied only on the macro steps that straddle a wavefront's diagonal;
 //   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
 //     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
 //     and the transposing LDS read (ds_read_b64_tr_b16) delivers V^T in exactly that order.
