@@ -165,3 +165,23 @@ def test_bench_workloads_sampled(which):
     assert per_row.max() <= 2 * gh.REL_L2_TOL, per_row.max()
     print(f"prefill bench workload {which}: {len(picks)} rows, max_abs {err[0]:.2e}, rel_l2 {err[1]:.2e}, "
           f"worst row {per_row.max():.2e}")
+
+
+def test_scores_that_keep_rising_exercise_the_lazy_reference_maximum():
+    """Scores that grow with the key index: slowly (the reference maximum of the online softmax stays behind
+    the true one for a few steps and the weights exceed 1), fast (it moves at every step) and with a large
+    overall range; also a strongly negative trend (the first key dominates)."""
+    lens, qlens = [700, 700, 300, 520], [700, 130, 300, 7]
+    w, cpu, q, lens, qlens = make_case(lens, qlens, 8, 2, seed=21)
+    slopes = [0.05, 1.0, -0.7, 0.013]
+    bt = cpu.block_table.numpy()
+    q[:] = 0
+    q[:, :, 0] = 8.0
+    for b, (L, slope) in enumerate(zip(lens, slopes)):
+        t = torch.arange(int(L))
+        pages = torch.from_numpy(bt[b, : (int(L) + 15) // 16].astype(np.int64))[t // 16]
+        cpu.k_pages[pages, :, t % 16, :] = 0
+        cpu.k_pages[pages, :, t % 16, 0] = (slope * t.float()).to(torch.bfloat16)[:, None]
+    case = (w, cpu, q, lens, qlens)
+    out, _ = run_gpu(*case)
+    print("rising scores:", gh.assert_parity(out, reference(*case), "rising scores"))
