@@ -31,3 +31,15 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".cpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower() or f == "workloads.py" and "oracle" in text.lower(), f
+
+
+def test_bench_settling_phase_terminates_and_reports():
+    """The untimed settling phase of bench.py stops after its patience or its cap, whatever the step does."""
+    import importlib, time, types
+    bench = importlib.import_module("bench")
+    fake_torch = types.SimpleNamespace(cuda=types.SimpleNamespace(synchronize=lambda: None))
+    calls = []
+    assert bench.settle(lambda i: calls.append(i), fake_torch, 0) == (0.0, 0) and not calls
+    t0 = time.perf_counter()
+    seconds, steps = bench.settle(lambda i: time.sleep(0.002), fake_torch, 0.5)
+    assert 0.5 <= seconds < 2.0 and steps > 10 and time.perf_counter() - t0 < 3.0
