@@ -25,9 +25,11 @@
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
 //   * online softmax in the log2 domain, one update per column and macro step, per-column state
-//     lane-local; the running maximum is a reference point that moves (maxima exchanged across
-//     lanes, accumulators rescaled) only when some score exceeds it by 8 log2 units; the causal
-//     mask is a select and is applied only on the macro steps that straddle a wavefront's diagonal;
+//     lane-local; the running "maximum" is only a reference point: the common path computes no
+//     maximum, it takes the weights against the reference point it has, and only when a lane's sum
+//     of weights passes 2^20 are the true maxima found (and exchanged across lanes), the reference
+//     point moved and the accumulators rescaled; the causal mask is a select and is applied only on
+//     the macro steps that straddle a wavefront's diagonal;
 //   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
 //     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
 //     and the transposing LDS read (ds_read_b64_tr_b16) delivers V^T in exactly that order.
@@ -55,7 +57,7 @@ constexpr int kPrefillThreads = 64 * kPrefillWaves;
 constexpr int kColTiles = kPrefillColTiles;
 constexpr int kStepKeys = 32;
 constexpr int kMacroKeys = kPrefillMacroKeys;
-constexpr float kRescaleSlack = 8.f;   // log2 units: weights up to 256 before the reference maximum moves
+constexpr float kSumLimit = 1048576.f;   // a lane's sum of weights beyond this moves the reference point of the softmax
 
 template <int D>
 __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4))) void paged_prefill_kernel(const PrefillParams p) {
@@ -218,27 +220,52 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
         bf16x8 pb[SUB][CT];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
-            float mx = -INFINITY;
+            if constexpr (decltype(masked)::value) {
 #pragma unroll
-            for (int sub = 0; sub < SUB; ++sub)
+                for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
+                    for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if constexpr (decltype(masked)::value) {
+                        for (int r = 0; r < 4; ++r) {
                             const int key = kMacroKeys * macro + 32 * sub + 16 * h + 4 * g4 + r;
                             s[sub][ct][h][r] = key <= pos[ct] ? s[sub][ct][h][r] : -INFINITY;
                         }
-                        mx = fmaxf(mx, s[sub][ct][h][r]);
+            }
+            // weights against the reference point m (scaled, log2 units), their sum, packed to bf16
+            auto weights = [&](float mref) __attribute__((always_inline)) -> float {
+                float sum = 0.f;
+#pragma unroll
+                for (int sub = 0; sub < SUB; ++sub) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        f32x2 pp;
+                        pp[0] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1)], p.scale_log2e, -mref));
+                        pp[1] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1) + 1], p.scale_log2e, -mref));
+                        sum += pp[0] + pp[1];
+                        w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
                     }
-            // m is kept in scaled (log2) units; the scale is positive, so raw scores order like scaled ones
-            mx *= p.scale_log2e;
-            // The running maximum is only a reference point: the result does not depend on it as long as
-            // nothing overflows, so it is moved (and the accumulators rescaled) only when some score
-            // exceeds it by more than kRescaleSlack, i.e. the weights stay below 2^kRescaleSlack.  On
-            // the first steps of a prompt the true maximum rises at almost every step; its small
-            // increments are not worth 64 multiplications and two cross-lane exchanges each.
-            if (__builtin_amdgcn_ballot_w64(mx > m[ct] + kRescaleSlack) != 0) {
+                    pb[sub][ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+                }
+                return sum;
+            };
+            // The reference point of the online softmax need not be the maximum: the result does not
+            // depend on it as long as nothing overflows.  The common path therefore computes no maximum at
+            // all; it takes the weights against the reference point it has and looks at their sum.  Only
+            // when some lane's sum is beyond kSumLimit (a weight above 2^20; on the first step, where the
+            // reference point is -inf, every weight is +inf or NaN) is the true maximum computed, the
+            // reference point moved, the accumulators rescaled and the weights taken again.
+            float sum = weights(m[ct]);
+            if (__builtin_amdgcn_ballot_w64(!(sum <= kSumLimit)) != 0) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int sub = 0; sub < SUB; ++sub)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[sub][ct][h][r]);
+                // the scale is positive, so raw scores order like scaled ones
+                mx *= p.scale_log2e;
                 mx = fmaxf(mx, xor_f32(mx, 16));
                 mx = fmaxf(mx, xor_f32(mx, 32));
                 const float m_new = fmaxf(m[ct], mx);
@@ -247,20 +274,7 @@ __global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
                 for (int e = 0; e < EV; ++e) acc[e][ct] *= alpha;
                 m[ct] = m_new;
-            }
-            float sum = 0.f;
-#pragma unroll
-            for (int sub = 0; sub < SUB; ++sub) {
-                uint32_t w[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    f32x2 pp;
-                    pp[0] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1)], p.scale_log2e, -m[ct]));
-                    pp[1] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1) + 1], p.scale_log2e, -m[ct]));
-                    sum += pp[0] + pp[1];
-                    w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-                }
-                pb[sub][ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+                sum = weights(m_new);
             }
             l[ct] += sum;
         }
