@@ -6,11 +6,20 @@ HBM: host re-plan of the sequence splits (oserve_plan_update), upload of the
 per-request records, the split kernel and the log-sum-exp merge kernel.
 
 Prints ONE JSON line on stdout: whole-job throughput as effective KV GB/s
-(valid-token K+V bytes per step / step time), the roofline of the dominant
-(split) kernel measured with HIP events on the launch stream, and the fp64
-oracle timed on the host cores on a bounded sample of the same workload.
+(valid-token K+V bytes per step / step time) of the heterogeneous mix (workload
+3), the roofline of the dominant (split) kernel measured with HIP events on the
+launch stream, the fp64 oracle timed on the host cores on a bounded sample of
+the same workload, the errors of the timed output against that oracle
+(`parity`), and - under `extra` - shorter measurements of the other benchmark
+workloads, the chunked-prefill kernel and the KV-block migration copies.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4] [--split-tokens T]
+Order of a measurement: W warm-up steps, a first timed block of K steps
+(`value_unsettled`), an untimed settling phase (the part's clocks ramp for
+seconds after idle), then the K timed steps `value` is computed from;
+`untimed_steps` counts everything that ran before those.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..8] [--split-tokens T] [--no-extra]
+                  [--prefill 0|1|2] [--migrate]
 """
 from __future__ import annotations
 
@@ -24,10 +33,12 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per launch of the split kernel (read + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# scaled by a plain copy of known size: profiles/split_kernel_cfg3_heterogeneous_mix.md.  Only the
-# workload that was profiled has an entry; the others report null.
-MEASURED_TRAFFIC_BYTES = {3: 3_397_209 * 2048 + 10_499 * 1024}
+# HBM bytes per launch of the split kernel (read + written) from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
+# scaled by a plain copy of known size.  A recorded profile value, not a measurement of the run that
+# prints it: it is reported only while the kernel and planner sources still hash to what they were when the
+# profile was taken and the plan has the same number of work items; otherwise `traffic` is null.
+RECORDED_TRAFFIC = {"config": 3, "bytes": 3_397_209 * 2048 + 10_499 * 1024, "work_items": 5192,
+                    "sources_sha16": "stale", "profile": "profiles/split_kernel_cfg3_heterogeneous_mix.md"}
 
 
 def parse_args():
@@ -51,6 +62,11 @@ def parse_args():
     ap.add_argument("--migrate", action="store_true",
                     help="instead of the decode benchmark, time the KV-block migration copies (gather into a staging "
                          "chunk, scatter into a target pool) of the long requests of the heterogeneous mix")
+    ap.add_argument("--no-extra", dest="extra", action="store_false",
+                    help="with the default workload, skip the side measurements (other configs, prefill, migration) "
+                         "that are attached under the `extra` key")
+    ap.add_argument("--extra-settle-seconds", type=float, default=6.0,
+                    help="cap of the settling phase of each side measurement")
     ap.add_argument("--cpu-token-heads", type=float, default=120e6,
                     help="size of the oracle's sample in (token, query head) pairs")
     return ap.parse_args()
@@ -69,8 +85,10 @@ def build_inputs(w, wl, torch):
     return sets, nbytes
 
 
-def cpu_baseline(inp, wl, torch, budget_token_heads):
-    """Time the oracle, as it stands, on whole requests of the batch until the budget is met."""
+def cpu_baseline(inp, wl, torch, budget_token_heads, gpu_out=None):
+    """Time the oracle, as it stands, on whole requests of the batch until the budget is met.  Returns the
+    baseline record and, if `gpu_out` (the output tensor of the timed steps) is given, the errors of its rows
+    of the sampled requests against what the oracle computed for them."""
     from oracle import paged_attention_oracle as oracle
     w = inp.workload
     lens = inp.context_lens_host
@@ -82,6 +100,7 @@ def cpu_baseline(inp, wl, torch, budget_token_heads):
         if acc >= budget_token_heads:
             break
     elapsed = 0.0
+    ref_rows = []
     for b in chosen:
         n = (int(lens[b]) + w.page_size - 1) // w.page_size
         ids = inp.block_table[b, :n].long()
@@ -91,15 +110,27 @@ def cpu_baseline(inp, wl, torch, budget_token_heads):
         bt = np.arange(n, dtype=np.int32)[None, :]
         cl = np.array([lens[b]], dtype=np.int32)
         t0 = time.perf_counter()
-        oracle.paged_decode_attn(q, k, v, bt, cl, inp.scale)
+        ref_rows.append(oracle.paged_decode_attn(q, k, v, bt, cl, inp.scale)[0])
         elapsed += time.perf_counter() - t0
     sample_bytes = wl.kv_bytes(lens[chosen], w.num_kv_heads, w.head_dim)
+    parity = None
+    if gpu_out is not None:
+        ref = np.stack(ref_rows)                                          # [requests, Hq, D] float64
+        got = gpu_out[torch.tensor(chosen, device=gpu_out.device)].cpu().double().numpy()
+        per_row = np.linalg.norm(got - ref, axis=2) / np.linalg.norm(ref, axis=2)
+        parity = {"max_abs": float(np.abs(got - ref).max()),
+                  "rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref)),
+                  "worst_row_rel_l2": float(per_row.max()),
+                  "rows": int(ref.shape[0] * ref.shape[1]), "requests": len(chosen), "of_requests": len(lens),
+                  "tolerance": {"max_abs": 1e-2, "rel_l2": 2e-3},
+                  "what": "output of the last timed step vs the fp64 oracle, every element of the sampled requests"}
+        parity["ok"] = bool(parity["max_abs"] <= 1e-2 and parity["rel_l2"] <= 2e-3 and np.isfinite(got).all())
     return {
         "value": sample_bytes / elapsed / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
         "sample": f"{len(chosen)} of {len(lens)} whole requests (all {w.num_q_heads} query heads, "
                   f"{int(lens[chosen].sum())} tokens, {sample_bytes / 1e9:.3f} GB of K+V) in {elapsed:.1f} s, "
                   f"single thread",
-    }
+    }, parity
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 peak
@@ -131,10 +162,31 @@ def settle(step, torch, max_s):
             return now - begin, n
 
 
-def bench_prefill(args, torch, binding, wl):
+def timed_block(step, n, torch):
+    """n steps bracketed by synchronisations: ms per step (the larger of wall clock and GPU events)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start.record()
+    for i in range(n):
+        step(i)
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = start.elapsed_time(stop)
+    return max(wall_ms, gpu_ms) / n, gpu_ms / n
+
+
+def common_fields(args, ms_per_step, untimed):
+    return {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "untimed_steps": untimed,
+            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "data": "synthetic"}
+
+
+def bench_prefill(args, torch, binding, wl, which):
     """One step = oserve_prefill_plan_update + the prefill kernel on inputs resident in HBM."""
-    name = wl.PREFILL_WORKLOAD_NAMES[args.prefill]
-    w, lens, qlens = wl.prefill_workload(args.prefill)
+    name = wl.PREFILL_WORKLOAD_NAMES[which]
+    w, lens, qlens = wl.prefill_workload(which)
     inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed + 1)
@@ -143,24 +195,16 @@ def bench_prefill(args, torch, binding, wl):
     plan = binding.PrefillPlan(lens, qlens, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
                                inp.block_table.shape[1], 0)
 
-    def step():
+    def step(i=0):
         plan.update(lens, qlens)
         binding.paged_prefill_attn(plan, q, inp.k_pages, inp.v_pages, inp.block_table, w.scale, out)
 
-    settle_s, settle_steps = settle(lambda i: step(), torch, args.settle_seconds)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    unsettled_ms, _ = timed_block(step, args.steps, torch)
+    settle_s, settle_steps = settle(step, torch, args.settle_seconds)
     plan.enable_timing(True)
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    start.record()
-    for _ in range(args.steps):
-        step()
-    stop.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = max(wall_ms, start.elapsed_time(stop)) / args.steps
+    ms_per_step, _ = timed_block(step, args.steps, torch)
     kernel_ms, cnt = plan.kernel_ms()
     plan.enable_timing(False)
     # 2 products x 2 flop x head_dim per (query token, visible key) and query head; query i of a request sees L - n + i + 1 keys
@@ -168,19 +212,20 @@ def bench_prefill(args, torch, binding, wl):
     flop = 4.0 * w.head_dim * w.num_q_heads * pairs
     value = flop / (ms_per_step * 1e-3) / 1e12
     achieved = flop / (kernel_ms * 1e-3) / 1e12
-    print(json.dumps({
-        "metric": "chunked-prefill attention TFLOP/s (causal, paged KV)", "value": round(value, 1), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"prefill{args.prefill}: {name}; 32q/8kv heads, head_dim 128, page 16, "
+    res = {"metric": "chunked-prefill attention TFLOP/s (causal, paged KV)", "value": round(value, 1), "unit": "TFLOP/s",
+           "value_unsettled": round(flop / (unsettled_ms * 1e-3) / 1e12, 1)}
+    res.update(common_fields(args, ms_per_step, args.warmup + args.steps + settle_steps))
+    res.update({
+        "dtype": "bf16",
+        "config": {"workload": f"prefill{which}: {name}; 32q/8kv heads, head_dim 128, page 16, "
                                f"{int(qlens.sum())} query tokens, {flop / 1e12:.3f} TFLOP per step",
                    "work_items": plan.num_work_items, "block_tokens": plan.block_tokens,
                    "settle_s": round(settle_s, 2), "settle_steps": settle_steps},
         "roofline": {"bound": "mfma", "kernel": "paged_prefill_kernel", "achieved": round(achieved, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": None, "avg_kernel_ms": round(kernel_ms, 5), "launches_timed": cnt,
-                     "algorithmic_flop_per_launch": flop},
-    }))
+                     "algorithmic_flop_per_launch": flop}})
+    return res
 
 
 def bench_migrate(args, torch, binding, wl):
@@ -208,71 +253,50 @@ def bench_migrate(args, torch, binding, wl):
     v_dst = torch.empty_like(k_dst)
     payload = 2 * n * w.num_kv_heads * w.page_size * w.head_dim * 2     # K and V bytes of the chunk
 
-    def step():
+    def step(i=0):
         m.gather(inp.k_pages, inp.v_pages, inp.block_table, 0, w.num_kv_heads, k_stage, v_stage)
         m.scatter(k_stage, v_stage, tt_dev, 0, k_dst, v_dst)
 
-    settle_s, settle_steps = settle(lambda i: step(), torch, args.settle_seconds)
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
+    unsettled_ms, _ = timed_block(step, args.steps, torch)
+    settle_s, settle_steps = settle(step, torch, args.settle_seconds)
     m.enable_timing(True)
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    start.record()
-    for _ in range(args.steps):
-        step()
-    stop.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = max(wall_ms, start.elapsed_time(stop)) / args.steps
+    ms_per_step, _ = timed_block(step, args.steps, torch)
     kernel_ms, cnt = m.kernel_ms()
     m.enable_timing(False)
     moved = 2 * payload                                    # every byte is read once and written once
     value = 2 * moved / (ms_per_step * 1e-3) / 1e9         # two copies per step
     achieved = moved / (kernel_ms * 1e-3) / 1e9
-    print(json.dumps({
-        "metric": "KV-block migration copy GB/s (bytes read + written)", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+    res = {"metric": "KV-block migration copy GB/s (bytes read + written)", "value": round(value, 1), "unit": "GB/s",
+           "value_unsettled": round(2 * moved / (unsettled_ms * 1e-3) / 1e9, 1)}
+    res.update(common_fields(args, ms_per_step, args.warmup + args.steps + settle_steps))
+    res.update({
+        "dtype": "u8",
         "config": {"workload": f"the {len(rows)} long requests of cfg3 ({int(mlens.sum())} tokens, {n} pages, "
                                f"{payload / 1e9:.3f} GB of K+V per layer chunk): gather to staging + scatter to a target pool",
                    "settle_s": round(settle_s, 2), "settle_steps": settle_steps},
         "roofline": {"bound": "hbm", "kernel": "kv_migrate_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "avg_kernel_ms": round(kernel_ms, 5), "launches_timed": cnt,
-                     "algorithmic_bytes_per_launch": moved},
-    }))
+                     "algorithmic_bytes_per_launch": moved}})
+    return res
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (nothing here is sharded across GPUs); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    from paper_2602_12151_amd import binding, workloads as wl
+def sources_sha16():
+    """Hash of the sources that decide the split kernel's memory traffic (kernel, planner)."""
+    import hashlib
+    h = hashlib.sha256()
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2602_12151_amd", "csrc")
+    for name in ("kernels.hip", "kernels.h", "plan.cpp", "plan.h"):
+        with open(os.path.join(root, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    torch.cuda.set_device(0)
-    if args.copy_probe:
-        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(args.steps):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes": args.copy_probe, "launches": args.steps}))
-        return
-    if args.prefill >= 0:
-        bench_prefill(args, torch, binding, wl)
-        return
-    if args.migrate:
-        bench_migrate(args, torch, binding, wl)
-        return
-    w = wl.WORKLOADS[args.config]
+
+def bench_decode(args, torch, binding, wl, config, with_cpu):
+    """One step = host re-plan + expand + split + merge kernels of workload `config` on inputs resident in HBM."""
+    w = wl.WORKLOADS[config]
     sets, nbytes = build_inputs(w, wl, torch)
     ops = [binding.DecodeAttention(s, split_tokens=args.split_tokens) for s in sets]
     plan0 = ops[0].plan
@@ -281,24 +305,15 @@ def main():
         j = i % len(sets)
         ops[j].step(sets[j], replan=True)
 
-    settle_s, settle_steps = settle(step, torch, args.settle_seconds)
+    # The contract's W warm-up steps and a first timed block of K steps (reported as value_unsettled), then the
+    # settling phase, then the K timed steps `value` is computed from.
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
+    unsettled_ms, _ = timed_block(step, args.steps, torch)
+    settle_s, settle_steps = settle(step, torch, args.settle_seconds)
     for op in ops:
         op.plan.enable_timing(True)
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    start.record()
-    for i in range(args.steps):
-        step(i)
-    stop.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = start.elapsed_time(stop)
-    ms_per_step = max(wall_ms, gpu_ms) / args.steps
-
+    ms_per_step, gpu_ms_per_step = timed_block(step, args.steps, torch)
     tot, cnt = 0.0, 0
     for op in ops:
         ms, n = op.plan.split_kernel_ms()
@@ -327,19 +342,26 @@ def main():
 
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     achieved = nbytes / (split_ms * 1e-3) / 1e9
-    result = {
-        "metric": "decode-attn effective KV GB/s (% of HBM peak) + us/step, mixed-length batch",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
+    traffic, traffic_note = None, "not profiled for this workload"
+    if config == RECORDED_TRAFFIC["config"] and args.split_tokens == 0:
+        if sources_sha16() == RECORDED_TRAFFIC["sources_sha16"] and plan0.num_work_items == RECORDED_TRAFFIC["work_items"]:
+            traffic, traffic_note = RECORDED_TRAFFIC["bytes"], "recorded rocprofv3 value of " + RECORDED_TRAFFIC["profile"]
+        else:
+            traffic_note = "kernel or planner sources changed since " + RECORDED_TRAFFIC["profile"] + " was taken"
+    result = {"metric": "decode-attn effective KV GB/s (% of HBM peak) + us/step, mixed-length batch",
+              "value": round(value, 1), "unit": "GB/s",
+              "value_unsettled": round(nbytes / (unsettled_ms * 1e-3) / 1e9, 1)}
+    result.update(common_fields(args, ms_per_step, args.warmup + args.steps + settle_steps))
+    result.update({
+        "us_per_step": round(ms_per_step * 1e3, 2),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16",
         "config": {"workload": f"cfg{w.index} {w.name}: batch {w.batch}, {w.num_q_heads}q/{w.num_kv_heads}kv heads, "
                                f"head_dim {w.head_dim}, page {w.page_size}, {int(sets[0].context_lens_host.sum())} tokens, "
                                f"{nbytes / 1e9:.3f} GB K+V per step",
-                   "work_items": plan0.num_work_items, "split_pages": plan0.split_pages,
+                   "work_items": plan0.num_work_items, "split_tokens": plan0.split_tokens,
                    "settle_s": round(settle_s, 2), "settle_steps": settle_steps,
-                   "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms / args.steps, 5),
+                   "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms_per_step, 5),
                    "single_step_us_median": round(singles[len(singles) // 2] * 1e3, 2),
                    "single_step_us_min": round(singles[0] * 1e3, 2),
                    "host_plan_update_us": round(plan_us, 2),
@@ -347,12 +369,86 @@ def main():
                              f"{prop.total_memory / 2**30:.0f} GiB"},
         "roofline": {"bound": "hbm", "kernel": "paged_decode_split_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.index) if args.split_tokens == 0 else None,
+                     "traffic": traffic, "traffic_note": traffic_note,
                      "avg_kernel_ms": round(split_ms, 5), "launches_timed": cnt,
-                     "algorithmic_bytes_per_launch": nbytes},
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(sets[0], wl, torch, args.cpu_token_heads)
+                     "algorithmic_bytes_per_launch": nbytes}})
+    if with_cpu:
+        # the output the last timed step of input set 0 left behind, against what the oracle computes below
+        step(0)
+        torch.cuda.synchronize()
+        result["cpu_baseline"], result["parity"] = cpu_baseline(sets[0], wl, torch, args.cpu_token_heads, ops[0].out)
+    return result
+
+
+def brief(res):
+    """The figures of a side measurement that go under the headline's `extra` key."""
+    r = res["roofline"]
+    out = {"value": res["value"], "unit": res["unit"], "value_unsettled": res["value_unsettled"],
+           "us_per_step": round(res["ms_per_step"] * 1e3, 2), "workload": res["config"]["workload"],
+           "kernel": r["kernel"], "kernel_achieved": r["achieved"], "kernel_frac_of_peak": r["frac"], "bound": r["bound"]}
+    if res["unit"] == "GB/s" and r["bound"] == "hbm":
+        out["pct_hbm_peak"] = round(100.0 * res["value"] / HBM_PEAK_GBS, 2)
+    for k in ("single_step_us_median", "ms_mixed", "ms_decode_then_prefill", "ms_decode_alone", "ms_prefill_alone",
+              "mixed_output_equals_separate_calls_bitwise"):
+        if k in res["config"]:
+            out[k] = res["config"][k]
+    if "also" in r:
+        out["also"] = {k: r["also"][k] for k in ("bound", "achieved", "unit", "frac")}
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (nothing here is sharded across GPUs); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import gc
+    import torch
+    from paper_2602_12151_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.empty(args.copy_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "launches": args.steps}))
+        return
+    if args.prefill >= 0:
+        print(json.dumps(bench_prefill(args, torch, binding, wl, args.prefill)))
+        return
+    if args.migrate:
+        print(json.dumps(bench_migrate(args, torch, binding, wl)))
+        return
+    result = bench_decode(args, torch, binding, wl, args.config, not args.no_cpu_baseline)
+    if args.extra and args.config == 3 and args.split_tokens == 0:
+        # Side measurements, shorter (their own settling cap): the other benchmark configs, the chunked-prefill
+        # kernel and the migration copies.  The headline fields above are not touched by them.
+        side = argparse.Namespace(**vars(args))
+        side.settle_seconds = min(args.settle_seconds, args.extra_settle_seconds)
+        extra = {}
+        t_extra = time.perf_counter()
+
+        def run(name, fn):
+            gc.collect()
+            torch.cuda.empty_cache()
+            try:
+                extra[name] = brief(fn())
+            except Exception as e:                 # a side measurement never costs the headline
+                extra[name] = {"error": f"{type(e).__name__}: {e}"}
+            print(f"bench.py: extra {name} done at {time.perf_counter() - t_extra:.1f} s", file=sys.stderr, flush=True)
+
+        for c in (0, 1, 2, 4):
+            run(f"cfg{c}", lambda c=c: bench_decode(side, torch, binding, wl, c, False))
+        for which in (0, 1, 2):
+            run(f"prefill{which}", lambda which=which: bench_prefill(side, torch, binding, wl, which))
+        run("kv_migration", lambda: bench_migrate(side, torch, binding, wl))
+        result["extra"] = extra
     print(json.dumps(result))
 
 

@@ -50,11 +50,12 @@ typedef struct oserve_plan oserve_plan_t;
 typedef enum {
     OSERVE_OK = 0,
     OSERVE_ERR_NULL = 1,          /* a required pointer is null */
-    OSERVE_ERR_SHAPE = 2,         /* unsupported head geometry, page size or batch */
+    OSERVE_ERR_SHAPE = 2,         /* unsupported head geometry, page size, batch or other size argument */
     OSERVE_ERR_CONTEXT_LEN = 3,   /* a context length < 1 or beyond the block-table width */
     OSERVE_ERR_WORKSPACE = 4,     /* workspace too small or misaligned */
     OSERVE_ERR_PLAN_MISMATCH = 5, /* batch larger than the plan's capacity, or plan has no device */
-    OSERVE_ERR_DEVICE = 6         /* a HIP runtime call failed */
+    OSERVE_ERR_DEVICE = 6,        /* a HIP runtime call failed */
+    OSERVE_ERR_ALIGNMENT = 7      /* a device pointer is not aligned as the call requires */
 } oserve_status_t;
 
 /* Launches a plan may have in flight before a launch call waits for the oldest. */
@@ -82,9 +83,9 @@ typedef enum {
  *   context_lens_host  [batch] int32, host memory, each in [1, max_pages_per_seq*page_size]
  *   max_pages_per_seq  row stride (entries) of the block table passed at launch
  *   split_tokens       0 = automatic; else a positive multiple of page_size
- *   device_id          HIP device whose compute-unit count sizes the splits and on
- *                      which the plan will be launched; -1 = no device (planning
- *                      only, assumes 256 compute units; such a plan cannot launch)
+ *   device_id          HIP device on which the plan will be launched; its compute-unit and
+ *                      SIMD counts (queried) size the splits; -1 = no device (planning
+ *                      only, assumes 256 compute units of 4 SIMDs; such a plan cannot launch)
  *   capacity           largest batch a later oserve_plan_update may bring (>= batch)
  *
  * Errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_CONTEXT_LEN, OSERVE_ERR_DEVICE.
@@ -109,8 +110,9 @@ void oserve_plan_destroy(oserve_plan_t* plan); /* null is allowed; the plan's la
 /* Plan queries (plan must be non-null). */
 int32_t oserve_plan_batch(const oserve_plan_t* plan);
 int32_t oserve_plan_num_work_items(const oserve_plan_t* plan); /* grid size of the split kernel */
-int32_t oserve_plan_split_pages(const oserve_plan_t* plan);    /* C, in pages */
-/* Splits of request b: their count, and the size in pages of the largest split of the batch.  Out pointers may be null. */
+int32_t oserve_plan_split_pages(const oserve_plan_t* plan);    /* C, in 16-token tiles */
+int32_t oserve_plan_split_tokens(const oserve_plan_t* plan);   /* C, in tokens (16 x the above) */
+/* Splits of request b: their count, and the size in 16-token tiles of its largest split.  Out pointers may be null. */
 oserve_status_t oserve_plan_request(const oserve_plan_t* plan, int32_t b, int32_t* num_splits,
                                     int32_t* max_split_pages);
 /* Inspection of the launch order: the plan holds oserve_plan_num_runs() runs, run i being `num_splits`
@@ -151,7 +153,7 @@ size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan);
  *   out            fp32 [batch, num_q_heads, head_dim], contiguous
  *
  * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_WORKSPACE, OSERVE_ERR_PLAN_MISMATCH,
- * OSERVE_ERR_DEVICE.  Not checkable without a device round trip, hence undefined
+ * OSERVE_ERR_ALIGNMENT (q, k_pages, v_pages or out not 16-byte aligned), OSERVE_ERR_DEVICE.  Not checkable without a device round trip, hence undefined
  * behaviour: block-table entries outside the pool.
  */
 oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
@@ -186,9 +188,7 @@ const char* oserve_status_string(oserve_status_t status);
  *
  * with r_b = q_lens[0] + ... + q_lens[b-1] (the queries of all requests packed one
  * after the other), kv head and k_t, v_t as for the decode call.  n_b = 1 is a
- * decode step; a whole prompt is n_b = L_b.  A mixed batch is served by running
- * its decode requests through oserve_paged_decode_attn and its prefill chunks
- * through this call on the same stream.
+ * decode step; a whole prompt is n_b = L_b.
  *
  * One workgroup of eight wavefronts handles a block of 256 / G query tokens of one
  * request against one kv head (G = num_q_heads / num_kv_heads); K and V tiles go
@@ -201,8 +201,8 @@ typedef struct oserve_prefill_plan oserve_prefill_plan_t;
 /*
  * Plan: the list of work items (block of query tokens x kv head).  The blocks of one
  * (request, kv head) read the same K/V; they are placed at launch indices that are
- * equal modulo 8 so that they run side by side on one of the device's 8 XCDs and
- * share its L2; (request, kv head) groups are dealt to the XCDs heaviest first.
+ * equal modulo the device's XCD count (queried; 8 without a device) so that they run
+ * side by side on one XCD and share its L2; (request, kv head) groups are dealt to the XCDs heaviest first.
  * Host-only.  It also owns the pinned staging through which the kernel reads that
  * list (OSERVE_PLAN_RING slots, same reuse rule as the decode plan).
  *
@@ -240,7 +240,7 @@ oserve_status_t oserve_prefill_plan_item(const oserve_prefill_plan_t* plan, int3
  *   block_table  int32 [batch, max_pages_per_seq]
  *   scale        multiplies the fp32 score; must be positive and finite
  *   out          fp32 [sum n_b, num_q_heads, head_dim], contiguous
- * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (alignment, scale), OSERVE_ERR_PLAN_MISMATCH
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (scale), OSERVE_ERR_ALIGNMENT, OSERVE_ERR_PLAN_MISMATCH
  * (plan without device), OSERVE_ERR_DEVICE.  Block-table entries outside the pool: undefined.
  */
 oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const void* q, const void* k_pages,
@@ -290,8 +290,8 @@ oserve_status_t oserve_kv_migration_request(const oserve_kv_migration_t* m, int3
  * gather reads rows table_rows_host[r] of `block_table`; scatter reads row r of `target_block_table`.
  * max_pages_per_seq is the row stride of the table and must cover the longest migrating request.
  * Pages the tables do not name, and heads outside [head_begin, head_begin + num_heads), are not touched.
- * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_PLAN_MISMATCH, OSERVE_ERR_DEVICE.
- * Table entries outside the pool, or two requests naming one target page: undefined.
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE, OSERVE_ERR_ALIGNMENT, OSERVE_ERR_PLAN_MISMATCH,
+ * OSERVE_ERR_DEVICE.  Table entries outside the pool, or two requests naming one target page: undefined.
  */
 oserve_status_t oserve_kv_gather(oserve_kv_migration_t* m, const void* k_pool, const void* v_pool,
                                  const int32_t* block_table, int32_t max_pages_per_seq, int32_t pool_kv_heads,
@@ -336,7 +336,7 @@ oserve_status_t oserve_switch_plan(int32_t num_devices, const int32_t* device_ma
                                    const int64_t* volumes, int32_t* chosen_source, int64_t* pair_load);
 
 /*
- * Edge capacity normalisation (section 4.1): the common capacity M of a replica that
+ * Edge capacity normalisation (section 4.2): the common capacity M of a replica that
  * can process per_type_capacity[j] requests of type j per unit time alone is the least
  * common multiple of those numbers (zeros = types it cannot serve are skipped); one
  * type-j request then consumes units_per_request[j] = M / per_type_capacity[j] units.
@@ -346,7 +346,7 @@ oserve_status_t oserve_capacity_normalise(const int64_t* per_type_capacity, int3
                                           int64_t* units_per_request);
 
 /*
- * Lower-level workload assignment (section 4.1): the assignment x[k][j] >= 0 of type-j
+ * Lower-level workload assignment (section 4.2): the assignment x[k][j] >= 0 of type-j
  * requests to replica k that serves the most requests subject to
  *   C1  sum_k x[k][j] <= arrivals[j]
  *   C2  x[k][j] <= edge_capacity[k][j]                 (skipped when edge_capacity is null or infinite)

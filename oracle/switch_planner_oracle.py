@@ -4,8 +4,8 @@
   Switching" (paper section 5.2) in its notation: counters C[s -> t] per device pair, shards in
   order, for each target that does not hold the shard the intra-machine holders if any, else the
   others, the one with the smallest C[s -> t] (first listed among equals), then C grows by V.
-* capacity_normalise: section 4.1's least common multiple M_k and per-request units M_k / n_kj.
-* assign_workload: section 4.1's constraints C1-C3 written out as a linear program and handed to
+* capacity_normalise: section 4.2's least common multiple M_k and per-request units M_k / n_kj.
+* assign_workload: section 4.2's constraints C1-C3 written out as a linear program and handed to
   scipy's linprog (the library primitive); the optimum value is what is compared.
 
 Pins (tests/test_switch_planner.py): the paper's own numbers 80 and 50 -> 400, 5 and 8; closed

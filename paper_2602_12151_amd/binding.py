@@ -14,7 +14,7 @@ import torch
 
 _LIB_PATH = os.environ.get("OSERVE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "liboserve.so")
 
-OK, ERR_NULL, ERR_SHAPE, ERR_CONTEXT_LEN, ERR_WORKSPACE, ERR_PLAN_MISMATCH, ERR_DEVICE = range(7)
+OK, ERR_NULL, ERR_SHAPE, ERR_CONTEXT_LEN, ERR_WORKSPACE, ERR_PLAN_MISMATCH, ERR_DEVICE, ERR_ALIGNMENT = range(8)
 PLAN_RING = 8
 
 
@@ -39,7 +39,8 @@ def _load() -> ctypes.CDLL:
     lib.oserve_plan_destroy.argtypes = [vp]
     lib.oserve_plan_run.restype = ctypes.c_int
     lib.oserve_plan_run.argtypes = [vp, i32, pi32]
-    for name in ("oserve_plan_batch", "oserve_plan_num_work_items", "oserve_plan_split_pages", "oserve_plan_num_runs"):
+    for name in ("oserve_plan_batch", "oserve_plan_num_work_items", "oserve_plan_split_pages", "oserve_plan_split_tokens",
+                 "oserve_plan_num_runs"):
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = [vp]
     lib.oserve_plan_request.restype = ctypes.c_int
@@ -121,6 +122,9 @@ class Plan:
                  device_id: int = 0, capacity: int | None = None):
         lens = _host_lens(context_lens_host)
         self._h = ctypes.c_void_p()
+        # the geometry the plan was built for: the launch wrapper checks its tensors against it
+        # (the C ABI carries no shapes)
+        self.geometry = (num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq)
         st = lib.oserve_plan_create(lens.ctypes.data, len(lens), num_q_heads, num_kv_heads, head_dim,
                                     page_size, max_pages_per_seq, split_tokens, device_id,
                                     len(lens) if capacity is None else capacity, ctypes.byref(self._h))
@@ -158,6 +162,10 @@ class Plan:
         return lib.oserve_plan_split_pages(self._h)
 
     @property
+    def split_tokens(self) -> int:
+        return lib.oserve_plan_split_tokens(self._h)
+
+    @property
     def workspace_bytes(self) -> int:
         return lib.oserve_plan_workspace_bytes(self._h)
 
@@ -166,7 +174,7 @@ class Plan:
         return lib.oserve_plan_workspace_bytes_max(self._h)
 
     def request(self, b: int):
-        """(num_splits of request b, pages of the largest split of the batch)."""
+        """(num_splits of request b, 16-token tiles of its largest split)."""
         s, p = ctypes.c_int32(), ctypes.c_int32()
         st = lib.oserve_plan_request(self._h, b, ctypes.byref(s), ctypes.byref(p))
         if st != OK:
@@ -205,22 +213,34 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def paged_decode_attn(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pages: torch.Tensor,
-                      v_pages: torch.Tensor, block_table: torch.Tensor, context_lens: torch.Tensor,
-                      scale: float, out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
-    """oserve_paged_decode_attn on torch tensors (layout checks only; no arithmetic here)."""
-    if not (q.is_cuda and k_pages.is_cuda and v_pages.is_cuda and block_table.is_cuda
-            and context_lens.is_cuda and out.is_cuda and workspace.is_cuda):
+def _check_decode_tensors(plan: Plan, q, k_pages, v_pages, block_table, context_lens, out, extra=()):
+    """Device, dtype, contiguity and shape checks of a decode launch against the plan's geometry."""
+    tensors = (q, k_pages, v_pages, block_table, context_lens, out) + tuple(extra)
+    if not all(t.is_cuda for t in tensors):
         raise ValueError("all tensors must be device tensors")
     if q.dtype != torch.bfloat16 or k_pages.dtype != torch.bfloat16 or v_pages.dtype != torch.bfloat16:
         raise TypeError("q / k_pages / v_pages must be bf16")
     if block_table.dtype != torch.int32 or context_lens.dtype != torch.int32 or out.dtype != torch.float32:
         raise TypeError("block_table / context_lens must be int32 and out fp32")
-    for t in (q, k_pages, v_pages, block_table, context_lens, out, workspace):
-        if not t.is_contiguous():
-            raise ValueError("tensors must be contiguous")
-    if k_pages.shape != v_pages.shape or out.shape != q.shape or block_table.shape[0] != q.shape[0]:
-        raise ValueError("shape mismatch")
+    if not all(t.is_contiguous() for t in tensors):
+        raise ValueError("tensors must be contiguous")
+    hq, hkv, d, page, width = plan.geometry
+    b = plan.batch
+    if tuple(q.shape) != (b, hq, d) or out.shape != q.shape:
+        raise ValueError(f"q / out must be [{b}, {hq}, {d}] for this plan, got {tuple(q.shape)} / {tuple(out.shape)}")
+    if k_pages.dim() != 4 or tuple(k_pages.shape[1:]) != (hkv, page, d) or v_pages.shape != k_pages.shape:
+        raise ValueError(f"k_pages / v_pages must be [pages, {hkv}, {page}, {d}] for this plan")
+    if tuple(block_table.shape) != (b, width):
+        raise ValueError(f"block_table must be [{b}, {width}] for this plan, got {tuple(block_table.shape)}")
+    if tuple(context_lens.shape) != (b,):
+        raise ValueError(f"context_lens must be [{b}] for this plan")
+
+
+def paged_decode_attn(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pages: torch.Tensor,
+                      v_pages: torch.Tensor, block_table: torch.Tensor, context_lens: torch.Tensor,
+                      scale: float, out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_decode_attn on torch tensors (layout checks only; no arithmetic here)."""
+    _check_decode_tensors(plan, q, k_pages, v_pages, block_table, context_lens, out, (workspace,))
     s = torch.cuda.current_stream(q.device) if stream is None else stream
     st = lib.oserve_paged_decode_attn(plan.handle, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
@@ -259,6 +279,8 @@ class PrefillPlan:
         if lens.shape != qlens.shape:
             raise ValueError("context_lens_host and q_lens_host must have the same length")
         self._h = ctypes.c_void_p()
+        self.geometry = (num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq)
+        self.batch = len(lens)
         st = lib.oserve_prefill_plan_create(lens.ctypes.data, qlens.ctypes.data, len(lens), num_q_heads, num_kv_heads,
                                             head_dim, page_size, max_pages_per_seq, device_id,
                                             len(lens) if capacity is None else capacity,
@@ -276,6 +298,7 @@ class PrefillPlan:
         st = lib.oserve_prefill_plan_update(self._h, lens.ctypes.data, qlens.ctypes.data, len(lens))
         if st != OK:
             raise OserveError(st, "oserve_prefill_plan_update")
+        self.batch = len(lens)
 
     @property
     def num_work_items(self) -> int:
@@ -329,8 +352,13 @@ def paged_prefill_attn(plan: PrefillPlan, q: torch.Tensor, k_pages: torch.Tensor
     for t in (q, k_pages, v_pages, block_table, out):
         if not t.is_contiguous():
             raise ValueError("tensors must be contiguous")
-    if k_pages.shape != v_pages.shape or out.shape != q.shape or q.shape[0] != plan.query_tokens:
-        raise ValueError("shape mismatch")
+    hq, hkv, d, page, width = plan.geometry
+    if tuple(q.shape) != (plan.query_tokens, hq, d) or out.shape != q.shape:
+        raise ValueError(f"q / out must be [{plan.query_tokens}, {hq}, {d}] for this plan")
+    if k_pages.dim() != 4 or tuple(k_pages.shape[1:]) != (hkv, page, d) or v_pages.shape != k_pages.shape:
+        raise ValueError(f"k_pages / v_pages must be [pages, {hkv}, {page}, {d}] for this plan")
+    if tuple(block_table.shape) != (plan.batch, width):
+        raise ValueError(f"block_table must be [{plan.batch}, {width}] for this plan")
     s = torch.cuda.current_stream(q.device) if stream is None else stream
     st = lib.oserve_paged_prefill_attn(plan.handle, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
                                        ctypes.c_float(scale), _ptr(out), ctypes.c_void_p(s.cuda_stream))

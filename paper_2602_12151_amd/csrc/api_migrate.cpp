@@ -6,6 +6,7 @@
 #include <new>
 #include <vector>
 
+#include "host_util.h"
 #include "kernels.h"
 #include "oserve.h"
 
@@ -17,39 +18,16 @@ struct oserve_kv_migration {
     int64_t num_pages = 0;
     std::vector<int32_t> offsets;   // [R + 1]
     int32_t* dev = nullptr;         // [num_pages][4]: source table row, request, page within the request, 0
-    hipEvent_t t_begin = nullptr, t_end = nullptr;
-    bool timing = false, t_pending = false;
-    double t_sum_ms = 0.0;
-    int64_t t_count = 0;
+    oserve::KernelTimer<1> timer;   // optional copy-kernel timing (the latest launch)
 };
 
 namespace {
 
-struct Guard {
-    int prev = -1, target = -1;
-    bool ok = true;
-    explicit Guard(int dev) : target(dev) {
-        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
-        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
-    }
-    ~Guard() { if (ok && prev != target) (void)hipSetDevice(prev); }
-};
+using Guard = oserve::DeviceGuard;
 
 void release(oserve_kv_migration* m) {
-    if (m->t_begin) (void)hipEventDestroy(m->t_begin);
-    if (m->t_end) (void)hipEventDestroy(m->t_end);
+    m->timer.destroy();
     if (m->dev) (void)hipFree(m->dev);
-}
-
-bool collect(oserve_kv_migration* m) {
-    if (!m->t_pending) return true;
-    if (hipEventSynchronize(m->t_end) != hipSuccess) return false;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, m->t_begin, m->t_end) != hipSuccess) return false;
-    m->t_sum_ms += ms;
-    m->t_count += 1;
-    m->t_pending = false;
-    return true;
 }
 
 oserve_status_t run(oserve_kv_migration* m, bool gather, const void* k_src, const void* v_src, void* k_dst,
@@ -61,10 +39,10 @@ oserve_status_t run(oserve_kv_migration* m, bool gather, const void* k_src, cons
     if (head_dim < 8 || head_dim % 8 != 0 || table_stride < m->max_request_pages) return OSERVE_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src) |
          reinterpret_cast<uintptr_t>(k_dst) | reinterpret_cast<uintptr_t>(v_dst)) & 15u)
-        return OSERVE_ERR_SHAPE;
+        return OSERVE_ERR_ALIGNMENT;
     Guard guard(m->device_id);
     if (!guard.ok) return OSERVE_ERR_DEVICE;
-    if (m->timing && !collect(m)) return OSERVE_ERR_DEVICE;
+    if (m->timer.enabled && !m->timer.collect(0)) return OSERVE_ERR_DEVICE;
     oserve::MigrateParams p{};
     p.k_src = k_src; p.v_src = v_src; p.k_dst = k_dst; p.v_dst = v_dst;
     p.block_table = table;
@@ -77,9 +55,9 @@ oserve_status_t run(oserve_kv_migration* m, bool gather, const void* k_src, cons
     p.num_heads = num_heads;
     p.unit_chunks = m->page_size * head_dim * 2 / 16;
     if (oserve::launch_kv_migrate(p, gather, static_cast<hipStream_t>(stream_v),
-                                  m->timing ? m->t_begin : nullptr, m->timing ? m->t_end : nullptr) != hipSuccess)
+                                  m->timer.begin_of(0), m->timer.end_of(0)) != hipSuccess)
         return OSERVE_ERR_DEVICE;
-    if (m->timing) m->t_pending = true;
+    m->timer.mark(0);
     return OSERVE_OK;
 }
 
@@ -128,7 +106,7 @@ oserve_status_t oserve_kv_migration_create(const int32_t* context_lens_host, con
             const size_t bytes = refs.size() * sizeof(int32_t);
             ok = ok && hipMalloc(reinterpret_cast<void**>(&m->dev), bytes) == hipSuccess;
             ok = ok && hipMemcpy(m->dev, refs.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
-            ok = ok && hipEventCreate(&m->t_begin) == hipSuccess && hipEventCreate(&m->t_end) == hipSuccess;
+            ok = ok && m->timer.create();
         }
         if (!ok) { release(m); delete m; return OSERVE_ERR_DEVICE; }
     }
@@ -172,20 +150,13 @@ oserve_status_t oserve_kv_scatter(oserve_kv_migration_t* m, const void* k_stage,
 oserve_status_t oserve_kv_migration_enable_timing(oserve_kv_migration_t* m, int32_t enable) {
     if (!m) return OSERVE_ERR_NULL;
     if (m->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
-    if (!collect(m)) return OSERVE_ERR_DEVICE;
-    m->timing = enable != 0;
-    m->t_sum_ms = 0.0;
-    m->t_count = 0;
-    return OSERVE_OK;
+    return m->timer.set_enabled(enable != 0) ? OSERVE_OK : OSERVE_ERR_DEVICE;
 }
 
 oserve_status_t oserve_kv_migration_kernel_ms(oserve_kv_migration_t* m, float* mean_ms, int32_t* count) {
     if (!m || !mean_ms || !count) return OSERVE_ERR_NULL;
     if (m->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
-    if (!collect(m)) return OSERVE_ERR_DEVICE;
-    *count = static_cast<int32_t>(m->t_count);
-    *mean_ms = m->t_count ? static_cast<float>(m->t_sum_ms / m->t_count) : 0.f;
-    return OSERVE_OK;
+    return m->timer.mean(mean_ms, count) ? OSERVE_OK : OSERVE_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -10,6 +10,7 @@ namespace oserve {
 
 struct SplitParams {
     const ItemDesc* items;         // one per work item, launch order
+    const RequestInfo* req_info;   // device copy, request order (read only where query rows are packed)
     const uint16_t* q;             // bf16 bits [B, Hq, D]
     const uint16_t* k_pages;       // bf16 bits [P, Hkv, page_size, D]
     const uint16_t* v_pages;
@@ -41,6 +42,11 @@ struct ExpandParams {
     int32_t num_kv_heads;
     uint32_t kv_heads_magic;          // floor(2^32 / num_kv_heads) + 1: (k * magic) >> 32 == k / num_kv_heads for k < 2^20
                                       // (unused when num_kv_heads == 1, where it does not fit 32 bits)
+    const void* blob_host;            // further records copied as they are (pinned host memory, 16-byte aligned) ...
+    void* blob;                       // ... into the workspace
+    int32_t blob_words;               // their size in 16-byte words (0: none)
+    int32_t* zero;                    // workspace words to clear (queue counters of the mixed kernel) ...
+    int32_t zero_words;               // ... and their number (0: none)
 };
 
 // The events are attached to the kernel's own dispatch (no marker packets between the kernels):
@@ -52,11 +58,12 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
 // ---- chunked prefill (prefill.hip) ----
-constexpr int kPrefillWaves = 8;        // wavefronts per workgroup (two per SIMD)
+constexpr int kPrefillWaves = 8;        // wavefronts per workgroup of the prefill kernel (two per SIMD)
+constexpr int kPrefillNarrowWaves = 4;  // wavefronts that share a prefill item in the mixed kernel (one per SIMD)
 constexpr int kPrefillColTiles = 2;     // 16-column score tiles per wavefront
 constexpr int kPrefillMacroKeys = 64;   // keys staged in LDS per barrier
-// query tokens of one work item for a GQA group of 1 << group_shift heads
-inline int prefill_block_tokens(int group_shift) { return kPrefillWaves * ((16 * kPrefillColTiles) >> group_shift); }
+// query tokens of one work item of a workgroup of `waves` wavefronts for a GQA group of 1 << group_shift heads
+inline int prefill_block_tokens(int group_shift, int waves = kPrefillWaves) { return waves * ((16 * kPrefillColTiles) >> group_shift); }
 
 // One workgroup's work: a block of query tokens of one request against one kv head.
 struct PrefillItem {
@@ -83,6 +90,24 @@ struct PrefillParams {
 
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
                           hipEvent_t start, hipEvent_t stop);
+
+// ---- mixed prefill + decode batches (mixed.hip) ----
+constexpr int kMaxQueueXcds = 16;   // prefill queues (one per XCD) the mixed kernel can address
+
+struct MixedParams {
+    SplitParams decode;       // items, req_info and partials in the workspace; q / out rows packed
+    PrefillParams prefill;    // items in the workspace: XCD 0's queue, then XCD 1's, ...
+    int32_t* queue_next;      // workspace, [kMaxQueueXcds + 1], zero at kernel start: next entry of each XCD's
+                              // prefill queue, then (index kMaxQueueXcds) of the decode queue
+    int32_t prefill_queue_first[kMaxQueueXcds];   // index of the first prefill item of each XCD's queue ...
+    int32_t prefill_queue_size[kMaxQueueXcds];    // ... and their number
+    int32_t num_xcds;
+    int32_t num_decode_items; // the decode queue is the decode items in launch order
+};
+
+// num_workgroups: two per compute unit (each lasts for the whole launch and takes work from the queues).
+hipError_t launch_mixed(const MixedParams& p, int head_dim, int num_workgroups, hipStream_t stream,
+                        hipEvent_t start, hipEvent_t stop);
 
 // ---- KV-block migration copies (migrate.hip) ----
 struct MigrateParams {

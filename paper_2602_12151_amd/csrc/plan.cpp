@@ -35,8 +35,7 @@ int64_t SplitPlan::max_items() const {
     return per_req * capacity * geo.num_kv_heads;
 }
 
-WorkspaceLayout SplitPlan::layout(int64_t items, int64_t row_groups, int64_t runs, int32_t n) const {
-    (void)runs;
+WorkspaceLayout SplitPlan::layout(int64_t items, int64_t row_groups, int32_t n) const {
     auto align = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
     WorkspaceLayout w{};
     w.req_info_off = 0;
@@ -54,30 +53,29 @@ inline int32_t round_up(int32_t x, int32_t g) { return (x + g - 1) / g * g; }
 
 }  // namespace
 
-oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
+oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n, const int32_t* q_lens) {
     if (!lens) return OSERVE_ERR_NULL;
     if (n < 1 || n > capacity) return OSERVE_ERR_PLAN_MISMATCH;
     const int64_t max_len = static_cast<int64_t>(geo.max_pages_per_seq) * geo.page_size;
     int64_t total_pages = 0;
     for (int32_t b = 0; b < n; ++b) {
         if (lens[b] < 1 || lens[b] > max_len) return OSERVE_ERR_CONTEXT_LEN;
-        total_pages += (lens[b] + kTileTokens - 1) / kTileTokens;
+        if (q_lens && (q_lens[b] < 1 || q_lens[b] > lens[b])) return OSERVE_ERR_CONTEXT_LEN;
+        if (!q_lens || q_lens[b] == 1) total_pages += (lens[b] + kTileTokens - 1) / kTileTokens;
     }
 
     // ---- size of the largest split, and the share of each long request that is tapered ----
     int32_t c = split_pages_user;
     int32_t taper_q8 = 0;
     if (c == 0) {
-        const int64_t slots = static_cast<int64_t>(num_cus) * kSlotsPerCu;
+        const int64_t slots = std::max<int64_t>(1, wave_slots);
         const int64_t units = total_pages * geo.num_kv_heads;
-        const int64_t target = std::max<int64_t>(1, slots * tuning.items_per_slot_x4 / 4);
-        int64_t want = (units + target - 1) / target;
-        want = std::min<int64_t>(tuning.max_split_pages, std::max<int64_t>(kSplitGranule, want));
+        const int64_t want = std::min<int64_t>(geo.max_tiles_per_seq(), std::max<int64_t>(kSplitGranule, (units + slots - 1) / slots));
         c = round_up(static_cast<int32_t>(want), kSplitGranule);
         // Work is handed out evenly only while an item is no longer than what is left per slot.
         // Full-size items therefore stop when about slots * C page-units are left, and from there
         // the splits shrink with what remains: that last share of every long request is tapered.
-        const int64_t q8 = units > 0 ? (16 * tuning.tail_slots_x16 * slots * c + units - 1) / units : 0;
+        const int64_t q8 = units > 0 ? (16 * kTailSlotsX16 * slots * c + units - 1) / units : 0;
         taper_q8 = static_cast<int32_t>(std::min<int64_t>(192, q8));
     }
     // ladder of split sizes for the tapered part
@@ -95,7 +93,15 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     recs.clear();
     info.resize(static_cast<size_t>(n));
     int64_t row_groups = 0;
+    int64_t q_row = 0;
+    bool any_split = false;
     for (int32_t b = 0; b < n; ++b) {
+        if (q_row > (1ll << 30)) return OSERVE_ERR_SHAPE;
+        if (q_lens && q_lens[b] != 1) {      // not a decode request: no runs
+            info[b] = RequestInfo{static_cast<int32_t>(row_groups), 0, static_cast<int32_t>(q_row), 0};
+            q_row += q_lens[b];
+            continue;
+        }
         const int32_t pages = (lens[b] + kTileTokens - 1) / kTileTokens;
         const size_t first_rec = recs.size();
         int32_t splits = 0;
@@ -139,8 +145,10 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
             }
         }
         for (size_t i = first_rec; i < recs.size(); ++i) recs[i].total_splits = splits;
-        info[b] = RequestInfo{static_cast<int32_t>(row_groups), splits};
+        info[b] = RequestInfo{static_cast<int32_t>(row_groups), splits, static_cast<int32_t>(q_lens ? q_row : b), 0};
+        q_row += 1;
         row_groups += splits;
+        any_split = any_split || splits > 1;
         if (recs.size() > static_cast<size_t>(max_runs())) return OSERVE_ERR_SHAPE;
     }
     // largest splits first; ties keep request order, so the launch order is deterministic
@@ -165,6 +173,7 @@ oserve_status_t SplitPlan::build(const int32_t* lens, int32_t n) {
     tail_q8 = taper_q8;
     num_items = static_cast<int32_t>(items);
     num_row_groups = static_cast<int32_t>(row_groups);
+    needs_merge = any_split;
     return OSERVE_OK;
 }
 

@@ -35,8 +35,11 @@ constexpr int32_t kKvHeadShift = 20;       // requests < 2^20, kv heads < 2^11
 
 struct RequestInfo {          // per request, in request order; read by the merge kernel
     int32_t split_base;       // first partial-result row group of the request
-    int32_t num_splits;
+    int32_t num_splits;       // 0: the request is not a decode request of this launch (mixed batches)
+    int32_t q_row;            // row of the request's query in q and out (= request index unless rows are packed)
+    int32_t pad;
 };
+static_assert(sizeof(RequestInfo) == 16, "record layout is part of the kernel interface");
 
 // The planner and the kernels work in tiles of kTileTokens tokens (one MFMA tile of keys); a page of
 // the cache holds 1, 2 or 4 of them.  Wherever this code says "pages" of a split, a run or an item
@@ -61,29 +64,24 @@ struct WorkspaceLayout {
 // C, C/2, C/4, ... >= kSplitGranule (each rounded up to the granule); a request contributes at most
 // kMaxRunsPerRequest runs.  Measured on the five workloads and modelled over scaled variants of
 // them, whole multiples or fractions of the fair share other than 1 leave slots idle at the end
-// (up to 20 % longer launches), so items_per_slot_x4 should stay 4.
+// (up to 20 % longer launches).
 constexpr int32_t kSplitGranule = 12;
 constexpr int32_t kMaxRunsPerRequest = 8;
-constexpr int32_t kSlotsPerCu = 4;
-
-struct PlanTuning {
-    int32_t items_per_slot_x4 = 4;   // full-size items per wavefront slot, in quarters
-    int32_t tail_slots_x16 = 6;      // tapered share = this/16 * slots * C page-units (see build())
-    int32_t max_split_pages = 1 << 26;  // optional cap on C (none by default)
-};
+constexpr int32_t kTailSlotsX16 = 6;        // tapered share = this/16 * slots * C page-units (see build())
+constexpr int32_t kDefaultWaveSlots = 1024; // plans without a device: 256 compute units x 4 SIMDs
 
 // Pure host logic (no HIP): everything the CPU tests exercise.
 struct SplitPlan {
     Geometry geo{};
     int32_t capacity = 0;
     int32_t split_pages_user = 0;   // 0 = automatic
-    int32_t num_cus = 256;
-    PlanTuning tuning{};
+    int32_t wave_slots = kDefaultWaveSlots;   // wavefronts the split kernel keeps resident: compute units x SIMDs
     int32_t batch = 0;
     int32_t split_pages = 0;        // C actually used
     int32_t tail_q8 = 0;            // share of each long request that is tapered, in 1/256 (0: none)
     int32_t num_items = 0;
     int32_t num_row_groups = 0;     // sum of splits over all requests
+    bool needs_merge = false;       // some request has more than one split
     std::vector<RunRecord> records;         // launch order
     std::vector<RequestInfo> req_info;      // request order
     std::vector<RunRecord> scratch_records; // build() works here, then swaps
@@ -92,8 +90,11 @@ struct SplitPlan {
     static oserve_status_t check_geometry(const Geometry& g, int32_t batch, int32_t capacity,
                                           int32_t split_tokens);
     void reserve();
-    oserve_status_t build(const int32_t* lens, int32_t n);
-    WorkspaceLayout layout(int64_t items, int64_t row_groups, int64_t runs, int32_t n) const;
+    // q_lens == nullptr: every request is a decode request and its query row is its index.  Otherwise
+    // request b brings q_lens[b] query rows packed after those of the requests before it, and only
+    // the requests with q_lens[b] == 1 are planned here (the others get num_splits = 0 and no runs).
+    oserve_status_t build(const int32_t* lens, int32_t n, const int32_t* q_lens = nullptr);
+    WorkspaceLayout layout(int64_t items, int64_t row_groups, int32_t n) const;
     int64_t max_items() const;
     int64_t max_runs() const { return static_cast<int64_t>(capacity) * kMaxRunsPerRequest; }
 };

@@ -1,6 +1,6 @@
 // Host-side planners of the serving method (no GPU code): the greedy switch plan of the appendix
 // "Greedy Algorithm for Ad Hoc Model Switching" (section 5.2), and the lower-level workload
-// assignment of section 4.1 (flow network with normalised replica capacities, constraints C1-C3).
+// assignment of section 4.2 (flow network with normalised replica capacities, constraints C1-C3).
 #include <algorithm>
 #include <cmath>
 #include <cstdint>

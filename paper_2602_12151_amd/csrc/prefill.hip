@@ -1,389 +1,17 @@
-// gfx950 kernel: causal chunked-prefill attention over the paged KV cache.
-//
-// What is computed: the prefill side of paper section 2 ("Phases of LLM inference": the prompt's
-// tokens are processed in parallel, compute-bound), in the form a serving engine runs it next to
-// decode steps: request b brings n_b new query tokens whose keys/values are already the last n_b
-// of its L_b cached tokens; query token i sits at position p = L_b - n_b + i and attends to the
-// cached tokens 0..p.  n_b = 1 is a decode step.
-//
-// How, on CDNA4: one workgroup of eight wavefronts (two per SIMD, so that one wavefront's MFMAs
-// overlap the other's softmax arithmetic) per (request, kv head, block of query tokens).  Every
-// wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
-// workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
-//   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
-//     (buffer loads with the LDS flag, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
-//     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
-//     stored XOR-swizzled.  A 16-byte-per-lane LDS read is served 16 lanes at a time (measured:
-//     lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, the same in the upper
-//     half), and those 16 must hit 16 different chunk positions of the 256-byte bank row: K chunks
-//     are XOR-ed with the key index (lane l fetches chunk (l % 16) ^ key).  V is read with the
-//     transposing 8-byte read, 32 lanes served together: V chunks are XOR-ed with 2 (key % 8).
-//     One barrier per kMacroKeys keys; the loads of the
-//     next macro step are in flight during the current one;
-//     half of the wavefronts run their softmax and value phases one macro step late, so that on
-//     every SIMD one wavefront's MFMAs overlap the other's softmax arithmetic;
-//   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
-//     registers as the B operand for the whole item);
-//   * online softmax in the log2 domain, one update per column and macro step, per-column state
-//     lane-local; the running "maximum" is only a reference point: the common path computes no
-//     maximum, it takes the weights against the reference point it has, and only when a lane's sum
-//     of weights passes 2^20 are the true maxima found (and exchanged across lanes), the reference
-//     point moved and the accumulators rescaled; the causal mask is a select and is applied only on
-//     the macro steps that straddle a wavefront's diagonal;
-//   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
-//     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
-//     and the transposing LDS read (ds_read_b64_tr_b16) delivers V^T in exactly that order.
-// Accumulation is fp32; P is rounded to bf16 for the second product.
-#include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
-
-#include <cstdint>
-#include <type_traits>
-
-#include "kernels.h"
+// gfx950 kernel: causal chunked-prefill attention over the paged KV cache (one workgroup per work
+// item; the work itself is in prefill_body.h, shared with the mixed prefill + decode kernel).
+#include "prefill_body.h"
 
 namespace oserve {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
-
-constexpr int kPrefillThreads = 64 * kPrefillWaves;
-constexpr int kColTiles = kPrefillColTiles;
-constexpr int kStepKeys = 32;
-constexpr int kMacroKeys = kPrefillMacroKeys;
-constexpr float kSumLimit = 1048576.f;   // a lane's sum of weights beyond this moves the reference point of the softmax
-
 template <int D>
-__global__ __launch_bounds__(kPrefillThreads) __attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4))) void paged_prefill_kernel(const PrefillParams p) {
-    static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
-    constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
-    constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
-    constexpr int ROW = D * 2;           // bytes of one key's row in LDS; chunk c of key k sits at slot c ^ (k % 16)
-    constexpr int TILE = kMacroKeys * ROW;
-    constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
-    constexpr int CT = kColTiles;
-    __shared__ __align__(16) unsigned char lds_k[2][TILE];   // K tiles: double-buffered
-    __shared__ __align__(16) unsigned char lds_v[3][TILE];   // V tiles: one more, for the wavefronts that run a macro step late
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int i16 = lane & 15;
-    const int g4 = lane >> 4;
-
-    // ---- the item: read by every lane from pinned host memory, then made wave-uniform ----
-    const PrefillItem* ip = p.items + blockIdx.x;
-    const int b = __builtin_amdgcn_readfirstlane(ip->request);
-    const int kvh = __builtin_amdgcn_readfirstlane(ip->kv_head);
-    const int q_begin = __builtin_amdgcn_readfirstlane(ip->q_begin);
-    const int q_row0 = __builtin_amdgcn_readfirstlane(ip->q_row0);   // packed row of the request's query 0
-    const int L = __builtin_amdgcn_readfirstlane(ip->context_len);
-    const int n = __builtin_amdgcn_readfirstlane(ip->q_len);
-
-    const int gshift = p.group_shift;
-    const int rt = (16 * CT) >> gshift;               // query tokens per wavefront
-    const int tok0 = q_begin + wave * rt;             // this wavefront's first query token
-    const int first_pos = L - n;                      // position of the request's query 0
-    // columns c = 16*ct + i16  ->  token tok0 + (c >> gshift), head c & (G-1); tokens past the
-    // request's last one are computed as copies of it and not stored
-    int tok[CT], pos[CT];
-    bf16x8 qf[CT][KK];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-        const int c = 16 * ct + i16;
-        tok[ct] = tok0 + (c >> gshift);
-        const int t_eff = min(tok[ct], n - 1);
-        pos[ct] = first_pos + t_eff;
-        const int head = kvh * p.group + (c & (p.group - 1));
-        const uint16_t* qrow = p.q + (static_cast<int64_t>(q_row0 + t_eff) * p.num_q_heads + head) * D;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
-            qf[ct][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow + (4 * kk + g4) * 8));
-    }
-    const int pos_min = first_pos + min(tok0, n - 1);             // wave-uniform
-    const int pos_max = first_pos + min(tok0 + rt - 1, n - 1);
-    const int blk_last = min(q_begin + kPrefillWaves * rt, n) - 1;   // last query token of the block
-    const int num_steps = (first_pos + blk_last) / kStepKeys + 1; // keys 0..pos of that token
-
-    // ---- where the 16-token tiles live (same walk as the decode kernel) ----
-    const int32_t* bt_row = p.block_table + static_cast<int64_t>(b) * p.max_pages_per_seq;
-    const int last_tile = (L - 1) >> 4;
-    const int tile_mask = (1 << p.tile_shift) - 1;
-    const int64_t page_elems = (static_cast<int64_t>(p.num_kv_heads) * 16 * D) << p.tile_shift;
-    const int64_t head_off = (static_cast<int64_t>(kvh) * 16 * D) << p.tile_shift;
-
-    // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
-    // of 4 KB into LDS.  Wavefront w fetches tile w % TILES of K (w < TILES) or V, one quarter (four
-    // keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk (l % 16) ^ key for K
-    // and chunk l % 16 for V. ----
-    constexpr int TILES = kMacroKeys / 16;
-    static_assert(kPrefillWaves == 2 * TILES, "one wavefront per staged tile");
-    const int st_tile = wave % TILES;
-    const bool st_is_v = wave >= TILES;
-    const uint16_t* st_pool = st_is_v ? p.v_pages : p.k_pages;
-    int st_lane_off[4];                    // byte offset of this lane's chunk within the tile, per quarter
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int key = 4 * q + (lane >> 4);
-        st_lane_off[q] = (key * D + (((lane & 15) ^ (st_is_v ? 2 * (key & 7) : key)) * 8)) * 2;
-    }
-    // V is read back with the transposing 8-byte LDS read: in each group of 16 lanes, lane s supplies
-    // the address of four consecutive dims (4 (s % 4) ..) of key 4 g4 + s / 4, and lane i receives dim i
-    // of the four keys.  The 16-byte chunks of a V row are stored XOR-ed with 2 (key % 8), which spreads
-    // the 32 lanes served together over all banks.
-    int v_off[EV];
-    {
-        const int key = 4 * g4 + (i16 >> 2);
-        const int t = ((i16 & 3) >> 1) ^ (2 * (key & 7));
-#pragma unroll
-        for (int e = 0; e < EV; ++e) v_off[e] = key * ROW + ((2 * e) ^ t) * 16 + (i16 & 1) * 8;
-    }
-    // The page id of a tile is loaded one macro step before the tile loads that need it and is only
-    // looked at (made wave-uniform) right before them, after the barrier in between has waited for
-    // it anyway: no wait for it of its own.
-    int next_pid, next_in_page;
-    auto fetch_base = [&](int macro) {   // clamped: never reads a table entry the request does not own
-        const int t = min(TILES * macro + st_tile, last_tile);
-        next_pid = bt_row[t >> p.tile_shift];
-        next_in_page = (t & tile_mask) * (16 * D);
-    };
-    auto stage_of = [&](int macro) -> unsigned char* {   // where this wavefront's tile of macro step `macro` goes
-        return (st_is_v ? lds_v[macro % 3] : lds_k[macro & 1]) + st_tile * 16 * ROW;
-    };
-    // loads of the macro step whose page id was fetched last
-    auto prefetch = [&](unsigned char* dst, const uint16_t* pool) __attribute__((always_inline)) {
-        const int64_t next_base = static_cast<int64_t>(__builtin_amdgcn_readfirstlane(next_pid)) * page_elems +
-                                  head_off + next_in_page;
-        // The tile is addressed through a buffer descriptor of its own (base = the tile, 4 KB long): a
-        // buffer load into LDS counts only in the vector-memory counter, whereas the compiler treats a
-        // global load into LDS as outstanding in the LDS counter as well and then makes every wait for
-        // an LDS read a wait for all of them.
-        const uintptr_t tile = reinterpret_cast<uintptr_t>(pool + next_base);
-        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(tile));
-        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(tile >> 32));
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            reinterpret_cast<void*>((static_cast<uintptr_t>(hi) << 32) | lo), 0, 16 * ROW, 0x00020000);
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
-                                                     16, st_lane_off[q], 0, 0, 0);
-    };
-
-    f32x4 acc[EV][CT];
-#pragma unroll
-    for (int e = 0; e < EV; ++e)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) acc[e][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m[CT], l[CT];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) { m[ct] = -INFINITY; l[ct] = 0.f; }
-
-    // One macro step for this wavefront's 16*CT columns runs in three phases, so that the MFMAs of a
-    // phase are issued back to back: (1) all scores of the kMacroKeys keys, (2) one online-softmax
-    // update per column over all of them, (3) the value products.
-    f32x4 s[SUB][CT][2];     // scores; lane (i16, g4) holds, for column i16 of tile ct, keys 32*sub + 16*h + 4*g4 + r
-    auto scores = [&](const unsigned char* kt) __attribute__((always_inline)) {
-#pragma unroll
-        for (int sub = 0; sub < SUB; ++sub)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                bf16x8 kf[KK];
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk)
-                    kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                        kt + (32 * sub + 16 * h + i16) * ROW + (((4 * kk + g4) ^ i16) * 16)));
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[ct][kk], a, 0, 0, 0);
-                    s[sub][ct][h] = a;
-                }
-            }
-        // order of this block's K reads and MFMAs: the fragments of two 16-key halves in flight, then
-        // per half its MFMAs followed by the reads of the half after the next
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * KK, 0);
-#pragma unroll
-        for (int i = 0; i < 2 * SUB - 2; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, CT * KK, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, KK, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * CT * KK, 0);
-    };
-    auto softmax_and_values = [&](int macro, const unsigned char* vt, auto masked) __attribute__((always_inline)) {
-        bf16x8 pb[SUB][CT];
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            if constexpr (decltype(masked)::value) {
-#pragma unroll
-                for (int sub = 0; sub < SUB; ++sub)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int key = kMacroKeys * macro + 32 * sub + 16 * h + 4 * g4 + r;
-                            s[sub][ct][h][r] = key <= pos[ct] ? s[sub][ct][h][r] : -INFINITY;
-                        }
-            }
-            // weights against the reference point m (scaled, log2 units), their sum, packed to bf16
-            auto weights = [&](float mref) __attribute__((always_inline)) -> float {
-                float sum = 0.f;
-#pragma unroll
-                for (int sub = 0; sub < SUB; ++sub) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        f32x2 pp;
-                        pp[0] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1)], p.scale_log2e, -mref));
-                        pp[1] = __builtin_amdgcn_exp2f(fmaf(s[sub][ct][j >> 1][2 * (j & 1) + 1], p.scale_log2e, -mref));
-                        sum += pp[0] + pp[1];
-                        w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-                    }
-                    pb[sub][ct] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
-                }
-                return sum;
-            };
-            // The reference point of the online softmax need not be the maximum: the result does not
-            // depend on it as long as nothing overflows.  The common path therefore computes no maximum at
-            // all; it takes the weights against the reference point it has and looks at their sum.  Only
-            // when some lane's sum is beyond kSumLimit (a weight above 2^20; on the first step, where the
-            // reference point is -inf, every weight is +inf or NaN) is the true maximum computed, the
-            // reference point moved, the accumulators rescaled and the weights taken again.
-            float sum = weights(m[ct]);
-            if (__builtin_amdgcn_ballot_w64(!(sum <= kSumLimit)) != 0) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int sub = 0; sub < SUB; ++sub)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[sub][ct][h][r]);
-                // the scale is positive, so raw scores order like scaled ones
-                mx *= p.scale_log2e;
-                mx = fmaxf(mx, xor_f32(mx, 16));
-                mx = fmaxf(mx, xor_f32(mx, 32));
-                const float m_new = fmaxf(m[ct], mx);
-                const float alpha = __builtin_amdgcn_exp2f(m[ct] - m_new);
-                l[ct] *= alpha;
-#pragma unroll
-                for (int e = 0; e < EV; ++e) acc[e][ct] *= alpha;
-                m[ct] = m_new;
-                sum = weights(m_new);
-            }
-            l[ct] += sum;
-        }
-        // value products: contraction index 8*g4 + j  <->  key 32*sub + 16*(j/4) + 4*g4 + j%4.  One
-        // transposing read hands lane (i16, g4) the values of dim 16*e + i16 at keys 4*g4 .. 4*g4+3 of
-        // one 16-key half: half of the A operand of tile e, no permutes.
-#pragma unroll
-        for (int sub = 0; sub < SUB; ++sub) {
-#pragma unroll
-            for (int e = 0; e < EV; ++e) {
-                s16x4 half[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    half[h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4*)(vt + (32 * sub + 16 * h) * ROW + v_off[e]));
-                    if constexpr (decltype(masked)::value) {
-                        // keys at or beyond the context may hold anything; their probabilities are zero, but a
-                        // NaN would survive the product, so their values are zeroed
-                        const int key0 = kMacroKeys * macro + 32 * sub + 16 * h + 4 * g4;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            if (key0 + r >= L) half[h][r] = 0;
-                    }
-                }
-                const bf16x8 av = __builtin_bit_cast(bf16x8, __builtin_shufflevector(half[0], half[1], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    acc[e][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[sub][ct], acc[e][ct], 0, 0, 0);
-            }
-        }
-        if constexpr (!decltype(masked)::value) {
-            // Order of this block's LDS reads and MFMAs: kAhead reads in flight, then two MFMAs (one row
-            // tile, both column tiles) per two reads, so that a read is waited for only after the MFMAs
-            // of several earlier tiles have been issued, not right after its own issue.
-            constexpr int kReads = 2 * EV * SUB, kAhead = 8;
-            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
-#pragma unroll
-            for (int i = 0; i < (kReads - kAhead) / 2; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, CT, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, CT * kAhead / 2, 0);
-        }
-    };
-    using Plain = std::integral_constant<bool, false>;
-    using Masked = std::integral_constant<bool, true>;
-    // phases 2 and 3 of macro step `macro`, if any of its keys is visible to this wavefront
-    auto finish = [&](int macro, const unsigned char* vt) __attribute__((always_inline)) {
-        const int first_key = kMacroKeys * macro;
-        if (first_key + kMacroKeys - 1 > pos_min) softmax_and_values(macro, vt, Masked{});
-        else softmax_and_values(macro, vt, Plain{});
-    };
-
-    // ---- main loop: one barrier per macro step.  The two wavefronts that share a SIMD (w and
-    // w + 4) run out of phase: the late half finishes macro step M-1 (softmax arithmetic, then value
-    // MFMAs) while the early half computes the scores of macro step M (MFMAs, then its softmax), so
-    // that one's VALU phase overlaps the other's MFMA phases.  That is why V has a third LDS buffer.
-    const int num_macro = (num_steps + SUB - 1) / SUB;
-    const bool late = wave >= kPrefillWaves / 2;
-    // macro steps with a key visible to this wavefront: 0 .. my_macros-1
-    const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
-    // One macro step.  The tile loads it issues land in buffers that nobody reads before the next
-    // barrier; the pointers are declared non-overlapping so that the LDS reads of this step are not
-    // made to wait for those loads.
-    auto step = [&](int macro, unsigned char* __restrict__ dst, const uint16_t* __restrict__ pool,
-                    const unsigned char* __restrict__ kt, const unsigned char* __restrict__ vt)
-                    __attribute__((always_inline)) {
-        if (macro + 1 < num_macro) {
-            prefetch(dst, pool);
-            fetch_base(macro + 2);     // clamped to the request's last tile
-        }
-        if (!late) {
-            if (macro < my_macros) { scores(kt); finish(macro, vt); }
-        } else {
-            if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1, vt);
-            if (macro < my_macros) scores(kt);
-        }
-    };
-    fetch_base(0);
-    prefetch(stage_of(0), st_pool);
-    fetch_base(1);
-    __syncthreads();
-    for (int macro = 0; macro < num_macro; ++macro) {
-        step(macro, stage_of(macro + 1), st_pool, lds_k[macro & 1], lds_v[(macro + (late ? 2 : 0)) % 3]);
-        __syncthreads();               // also waits for this wavefront's tile loads
-    }
-    if (late && num_macro - 1 < my_macros) finish(num_macro - 1, lds_v[(num_macro - 1) % 3]);
-
-    // ---- write out: lane holds column i16 of each tile, dims 16*e + 4*g4 + r ----
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-        float l_tot = l[ct] + xor_f32(l[ct], 16);
-        l_tot += xor_f32(l_tot, 32);
-        const int c = 16 * ct + i16;
-        if (tok[ct] < n) {
-            const int head = kvh * p.group + (c & (p.group - 1));
-            float* dst = p.out + (static_cast<int64_t>(q_row0 + tok[ct]) * p.num_q_heads + head) * D + 4 * g4;
-            const float inv = 1.f / l_tot;
-#pragma unroll
-            for (int e = 0; e < EV; ++e) {
-                float4 o;
-                o.x = acc[e][ct][0] * inv;
-                o.y = acc[e][ct][1] * inv;
-                o.z = acc[e][ct][2] * inv;
-                o.w = acc[e][ct][3] * inv;
-                *reinterpret_cast<float4*>(dst + 16 * e) = o;
-            }
-        }
-    }
+__global__ __launch_bounds__(prefill_detail::kPrefillThreads)
+__attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4)))
+void paged_prefill_kernel(const PrefillParams p) {
+    __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D, kPrefillWaves>()];
+    prefill_detail::prefill_item_body<D, kPrefillWaves>(p, p.items + blockIdx.x, (prefill_detail::lds_byte*)lds,
+                                                        prefill_detail::WorkgroupBarrier{}, static_cast<int>(threadIdx.x) >> 6);
 }
 
 }  // namespace
@@ -392,7 +20,7 @@ hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, h
                           hipEvent_t start, hipEvent_t stop) {
     if (num_items <= 0) return hipSuccess;
     if (head_dim != 128) return hipErrorInvalidValue;
-    hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(kPrefillThreads), 0, stream,
+    hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
                           start, stop, 0, p);
     return hipGetLastError();
 }

@@ -65,3 +65,23 @@ def sampled_oracle_rows(inp_dev: wl.Inputs, pairs):
         cl = np.array([L], dtype=np.int32)
         rows.append(oracle.paged_decode_attn(q, k, v, bt, cl, inp_dev.scale)[0, 0])
     return np.stack(rows)
+
+
+def oracle_whole_batch(inp_dev: wl.Inputs, progress=None) -> np.ndarray:
+    """Oracle output [B, Hq, D] of a batch that lives on the GPU, request by request: only one request's pages
+    (input bits, never outputs) are on the host at a time, renumbered into a compact pool."""
+    w = inp_dev.workload
+    B = len(inp_dev.context_lens_host)
+    ref = np.empty((B, w.num_q_heads, w.head_dim), dtype=np.float64)
+    for b in range(B):
+        L = int(inp_dev.context_lens_host[b])
+        n = (L + w.page_size - 1) // w.page_size
+        ids = inp_dev.block_table[b, :n].long()
+        k = inp_dev.k_pages[ids].cpu()
+        v = inp_dev.v_pages[ids].cpu()
+        bt = np.arange(n, dtype=np.int32)[None, :]
+        ref[b] = oracle.paged_decode_attn(inp_dev.q[b:b + 1].cpu(), k, v, bt, np.array([L], dtype=np.int32),
+                                          inp_dev.scale)[0]
+        if progress and (b + 1) % progress == 0:
+            print(f"  oracle: {b + 1}/{B} requests", flush=True)
+    return ref

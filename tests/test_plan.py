@@ -39,6 +39,10 @@ def check_plan(plan, lens, hkv):
             assert row not in rows_seen
             rows_seen.add(row)
     assert items == plan.num_work_items
+    assert plan.split_tokens == 16 * plan.split_pages
+    for b in range(len(lens)):
+        mine = [min(r["pages_per_split"], r["page_end"] - r["page_begin"]) for r in runs if r["request"] == b]
+        assert plan.request(b)[1] == max(mine)          # the request's own largest split
     for c in covered:
         assert (c == 1).all()
     total_splits = sum(plan.request(b)[0] for b in range(len(lens)))

@@ -8,9 +8,9 @@ from oracle import switch_planner_oracle as po
 from paper_2602_12151_amd import binding, workloads as wl
 
 
-# ------------------------------------------------------------------ capacity normalisation (section 4.1)
+# ------------------------------------------------------------------ capacity normalisation (section 4.2)
 def test_the_papers_80_and_50_give_400_5_and_8():
-    """Section 4.1's example: 80 type-1 and 50 type-2 requests per unit time -> common capacity 400,
+    """Section 4.2's example: 80 type-1 and 50 type-2 requests per unit time -> common capacity 400,
     a type-1 request consumes 5 units, a type-2 request 8."""
     assert po.capacity_normalise([80, 50]) == (400, [5, 8])
     assert binding.capacity_normalise([80, 50]) == (400, [5, 8])
@@ -24,7 +24,7 @@ def test_normalise_skips_types_the_replica_cannot_serve_and_rejects_overflow():
         binding.capacity_normalise([3, -1])
 
 
-# ------------------------------------------------------------------ workload assignment (section 4.1)
+# ------------------------------------------------------------------ workload assignment (section 4.2)
 def test_assignment_closed_forms():
     # one replica, one type: min(arrivals, capacity, edge)
     for lam, n, e, want in [(30, 80, None, 30), (100, 80, None, 80), (100, 80, [[25.0]], 25)]:
