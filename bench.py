@@ -11,7 +11,8 @@ Prints ONE JSON line on stdout: whole-job throughput as effective KV GB/s
 launch stream, the fp64 oracle timed on the host cores on a bounded sample of
 the same workload, the errors of the timed output against that oracle
 (`parity`), and - under `extra` - shorter measurements of the other benchmark
-workloads, the chunked-prefill kernel and the KV-block migration copies.
+workloads, the chunked-prefill kernel, the KV-block migration copies and the
+mixed prefill + decode step.
 
 Order of a measurement: W warm-up steps, a first timed block of K steps
 (`value_unsettled`), an untimed settling phase (the part's clocks ramp for
@@ -19,7 +20,7 @@ seconds after idle), then the K timed steps `value` is computed from;
 `untimed_steps` counts everything that ran before those.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..8] [--split-tokens T] [--no-extra]
-                  [--prefill 0|1|2] [--migrate]
+                  [--prefill 0|1|2] [--migrate] [--mixed]
 """
 from __future__ import annotations
 
@@ -62,6 +63,9 @@ def parse_args():
     ap.add_argument("--migrate", action="store_true",
                     help="instead of the decode benchmark, time the KV-block migration copies (gather into a staging "
                          "chunk, scatter into a target pool) of the long requests of the heterogeneous mix")
+    ap.add_argument("--mixed", action="store_true",
+                    help="instead of the decode benchmark, time one mixed step (the decode requests of the heterogeneous "
+                         "mix + 8 prefill chunks of 512 tokens in one call) against the decode call followed by the prefill call")
     ap.add_argument("--no-extra", dest="extra", action="store_false",
                     help="with the default workload, skip the side measurements (other configs, prefill, migration) "
                          "that are attached under the `extra` key")
@@ -283,6 +287,92 @@ def bench_migrate(args, torch, binding, wl):
     return res
 
 
+def bench_mixed(args, torch, binding, wl):
+    """One step = oserve_mixed_plan_update + oserve_paged_mixed_attn on a batch that holds decode requests and
+    prefill chunks, against the same work done by the decode call followed by the prefill call."""
+    w, lens, qlens = wl.mixed_workload()
+    inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 1)
+    q = torch.randn(int(qlens.sum()), w.num_q_heads, w.head_dim, generator=gen, device="cuda").to(torch.bfloat16)
+    out = torch.empty(q.shape, dtype=torch.float32, device="cuda")
+    width = inp.block_table.shape[1]
+    geo = (w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size, width)
+    plan = binding.MixedPlan(lens, qlens, *geo, 0)
+    ws = torch.empty(plan.workspace_bytes_max, dtype=torch.uint8, device="cuda")
+    # the same work through the two separate calls: decode requests first in the batch, chunks after them
+    nd = int((qlens == 1).sum())
+    assert (qlens[:nd] == 1).all() and (qlens[nd:] > 1).all()
+    dplan = binding.Plan(lens[:nd], *geo, 0, 0)
+    dws = torch.empty(dplan.workspace_bytes_max, dtype=torch.uint8, device="cuda")
+    pplan = binding.PrefillPlan(lens[nd:], qlens[nd:], *geo, 0)
+    out2 = torch.empty_like(out)
+    bt_d, bt_p = inp.block_table[:nd].contiguous(), inp.block_table[nd:].contiguous()
+    cl_d = inp.context_lens[:nd].contiguous()
+    q_d, q_p, o_d, o_p = q[:nd], q[nd:], out2[:nd], out2[nd:]
+
+    def mixed(i=0):
+        plan.update(lens, qlens)
+        binding.paged_mixed_attn(plan, ws, q, inp.k_pages, inp.v_pages, inp.block_table, inp.context_lens, w.scale, out)
+
+    def decode_only(i=0):
+        dplan.update(lens[:nd])
+        binding.paged_decode_attn(dplan, dws, q_d, inp.k_pages, inp.v_pages, bt_d, cl_d, w.scale, o_d)
+
+    def prefill_only(i=0):
+        pplan.update(lens[nd:], qlens[nd:])
+        binding.paged_prefill_attn(pplan, q_p, inp.k_pages, inp.v_pages, bt_p, w.scale, o_p)
+
+    def separate(i=0):
+        decode_only()
+        prefill_only()
+
+    for _ in range(args.warmup):
+        mixed()
+        separate()
+    torch.cuda.synchronize()
+    same = bool(torch.equal(out, out2))
+    unsettled_ms, _ = timed_block(mixed, args.steps, torch)
+    settle_s, settle_steps = settle(mixed, torch, args.settle_seconds)
+    # alternate blocks of the two ways so that both see the same state of the part
+    t = {"mixed": [], "separate": [], "decode": [], "prefill": []}
+    for _ in range(3):
+        t["mixed"].append(timed_block(mixed, args.steps, torch)[0])
+        t["separate"].append(timed_block(separate, args.steps, torch)[0])
+        t["decode"].append(timed_block(decode_only, args.steps, torch)[0])
+        t["prefill"].append(timed_block(prefill_only, args.steps, torch)[0])
+    ms = {k: min(v) for k, v in t.items()}
+    plan.enable_timing(True)
+    timed_block(mixed, args.steps, torch)
+    kernel_ms, cnt = plan.kernel_ms()
+    plan.enable_timing(False)
+    kv_bytes = wl.kv_bytes(lens[:nd], w.num_kv_heads, w.head_dim)
+    pairs = sum(int(n) * (int(L) - int(n)) + int(n) * (int(n) + 1) // 2 for L, n in zip(lens[nd:], qlens[nd:]))
+    flop = 4.0 * w.head_dim * w.num_q_heads * pairs
+    res = {"metric": "mixed prefill+decode step: time of the decode call + the prefill call over time of the one mixed call",
+           "value": round(ms["separate"] / ms["mixed"], 4), "unit": "x",
+           "value_unsettled": round(ms["separate"] / unsettled_ms, 4)}
+    res.update(common_fields(args, ms["mixed"], 2 * args.warmup + args.steps + settle_steps))
+    res.update({
+        "dtype": "bf16",
+        "config": {"workload": f"mixed: the {nd} decode requests of cfg3 ({kv_bytes / 1e9:.3f} GB of K+V) + {len(lens) - nd} "
+                               f"prefill chunks of 512 tokens ending contexts in [2048, 16384] ({flop / 1e12:.3f} TFLOP); "
+                               f"32q/8kv heads, head_dim 128, page 16",
+                   "counts": plan.counts, "ms_mixed": round(ms["mixed"], 5), "ms_decode_then_prefill": round(ms["separate"], 5),
+                   "ms_decode_alone": round(ms["decode"], 5), "ms_prefill_alone": round(ms["prefill"], 5),
+                   "mixed_output_equals_separate_calls_bitwise": same,
+                   "settle_s": round(settle_s, 2), "settle_steps": settle_steps},
+        "roofline": {"bound": "hbm", "kernel": "paged_mixed_kernel", "achieved": round(kv_bytes / (kernel_ms * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(kv_bytes / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_kernel_ms": round(kernel_ms, 5), "launches_timed": cnt,
+                     "algorithmic_bytes_per_launch": kv_bytes,
+                     "also": {"bound": "mfma", "achieved": round(flop / (kernel_ms * 1e-3) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(flop / (kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                              "algorithmic_flop_per_launch": flop,
+                              "note": "the decode requests' K/V bytes and the prefill chunks' flop, both over the one kernel's time"}}})
+    return res
+
+
 def sources_sha16():
     """Hash of the sources that decide the split kernel's memory traffic (kernel, planner)."""
     import hashlib
@@ -425,6 +515,9 @@ def main():
     if args.migrate:
         print(json.dumps(bench_migrate(args, torch, binding, wl)))
         return
+    if args.mixed:
+        print(json.dumps(bench_mixed(args, torch, binding, wl)))
+        return
     result = bench_decode(args, torch, binding, wl, args.config, not args.no_cpu_baseline)
     if args.extra and args.config == 3 and args.split_tokens == 0:
         # Side measurements, shorter (their own settling cap): the other benchmark configs, the chunked-prefill
@@ -448,6 +541,7 @@ def main():
         for which in (0, 1, 2):
             run(f"prefill{which}", lambda which=which: bench_prefill(side, torch, binding, wl, which))
         run("kv_migration", lambda: bench_migrate(side, torch, binding, wl))
+        run("mixed", lambda: bench_mixed(side, torch, binding, wl))
         result["extra"] = extra
     print(json.dumps(result))
 

@@ -188,7 +188,8 @@ const char* oserve_status_string(oserve_status_t status);
  *
  * with r_b = q_lens[0] + ... + q_lens[b-1] (the queries of all requests packed one
  * after the other), kv head and k_t, v_t as for the decode call.  n_b = 1 is a
- * decode step; a whole prompt is n_b = L_b.
+ * decode step; a whole prompt is n_b = L_b.  A batch that holds decode requests
+ * next to prefill chunks is served by oserve_paged_mixed_attn below.
  *
  * One workgroup of eight wavefronts handles a block of 256 / G query tokens of one
  * request against one kv head (G = num_q_heads / num_kv_heads); K and V tiles go
@@ -249,6 +250,75 @@ oserve_status_t oserve_paged_prefill_attn(oserve_prefill_plan_t* plan, const voi
 /* Optional timing of the kernel, as oserve_plan_enable_timing / oserve_plan_split_kernel_ms. */
 oserve_status_t oserve_prefill_plan_enable_timing(oserve_prefill_plan_t* plan, int32_t enable);
 oserve_status_t oserve_prefill_plan_kernel_ms(oserve_prefill_plan_t* plan, float* mean_ms, int32_t* count);
+
+
+/* ---------------------------------------------------------------------------
+ * Mixed batches: decode requests and prefill chunks in one call (paper section 1 (i)
+ * and section 2, "Workload heterogeneity": the requests of one batch differ widely, short
+ * ones compute-bound and long ones memory-bound; section 2, "Phases of LLM inference":
+ * the compute-intensive prefill phase and the memory-bandwidth-bound decoding phase).
+ * Same definition as oserve_paged_prefill_attn: request b brings n_b = q_lens[b] query
+ * tokens, the rows of q and out are packed request after request, and query token i of
+ * request b attends causally to the cached tokens 0 .. L_b - n_b + i.  What differs is
+ * how the work is run: requests with n_b = 1 are decode requests and go through the
+ * split-sequence decode work items (HBM-bound, then the log-sum-exp merge), requests with
+ * n_b > 1 through the prefill work items (MFMA-bound), and ONE kernel holds both kinds at
+ * the same time on every compute unit: the launch has two workgroups of four wavefronts
+ * (one per SIMD) per compute unit, which last for the whole launch; the four wavefronts of
+ * the one work through a queue of prefill items together, those of the other each through
+ * a queue of decode items, so that every SIMD runs a prefill wavefront's MFMAs next to a
+ * decode wavefront's K/V stream.  When one queue runs dry its workgroups turn to the other.
+ * Supported shapes: as oserve_paged_prefill_attn (head_dim 128; G in {1, 2, 4, 8, 16}).
+ * ------------------------------------------------------------------------- */
+typedef struct oserve_mixed_plan oserve_mixed_plan_t;
+
+/*
+ * Plan (host-only): the decode work items of the requests with n_b = 1 (sized as by
+ * oserve_plan_create with split_tokens = 0, queued largest first) and the prefill work items
+ * of the others (blocks of 128 / G query tokens x kv heads, one queue per XCD so that the blocks
+ * of one (request, kv head) share an L2).  Arguments and errors as oserve_prefill_plan_create.
+ */
+oserve_status_t oserve_mixed_plan_create(const int32_t* context_lens_host, const int32_t* q_lens_host,
+                                         int32_t batch, int32_t num_q_heads, int32_t num_kv_heads,
+                                         int32_t head_dim, int32_t page_size, int32_t max_pages_per_seq,
+                                         int32_t device_id, int32_t capacity, int64_t max_query_tokens,
+                                         oserve_mixed_plan_t** plan_out);
+/* Re-plan in place; no allocation.  On error the plan keeps its previous contents. */
+oserve_status_t oserve_mixed_plan_update(oserve_mixed_plan_t* plan, const int32_t* context_lens_host,
+                                         const int32_t* q_lens_host, int32_t batch);
+void oserve_mixed_plan_destroy(oserve_mixed_plan_t* plan); /* null allowed; launches must have completed */
+int64_t oserve_mixed_plan_query_tokens(const oserve_mixed_plan_t* plan);   /* sum of n_b: rows of q and out */
+/* counts = {workgroups of the mixed kernel (= 2 x compute units), prefill work items, decode work items,
+ * prefill queues (= XCDs)}. */
+oserve_status_t oserve_mixed_plan_counts(const oserve_mixed_plan_t* plan, int32_t counts[4]);
+/* Prefill item i (queue after queue, each in the order it is worked through):
+ * fields = {queue, request, kv_head, q_begin, q_row0, context_len, q_len}. */
+oserve_status_t oserve_mixed_plan_prefill_item(const oserve_mixed_plan_t* plan, int32_t i, int32_t fields[7]);
+size_t oserve_mixed_plan_workspace_bytes(const oserve_mixed_plan_t* plan);
+size_t oserve_mixed_plan_workspace_bytes_max(const oserve_mixed_plan_t* plan);
+
+/*
+ * Enqueues on `stream`: the kernel that copies the plan's records from pinned host memory into
+ * `workspace` and clears the queue counters, the mixed kernel, and (if a decode request is split)
+ * the merge kernel.  Returns
+ * without waiting, allocates nothing (same staging-ring rule as oserve_paged_decode_attn).
+ *   workspace      device, >= oserve_mixed_plan_workspace_bytes(plan), 256-byte aligned, scratch
+ *   q              bf16 [sum n_b, num_q_heads, head_dim], contiguous, 16-byte aligned
+ *   k_pages, v_pages, block_table   as for oserve_paged_decode_attn
+ *   context_lens   int32 [batch], device copy of the lengths the plan was built from (read for the
+ *                  decode requests only, as in oserve_paged_decode_attn)
+ *   scale          multiplies the fp32 score; must be positive and finite
+ *   out            fp32 [sum n_b, num_q_heads, head_dim], contiguous
+ * Host-checked errors: OSERVE_ERR_NULL, OSERVE_ERR_SHAPE (scale), OSERVE_ERR_WORKSPACE,
+ * OSERVE_ERR_ALIGNMENT, OSERVE_ERR_PLAN_MISMATCH, OSERVE_ERR_DEVICE.
+ */
+oserve_status_t oserve_paged_mixed_attn(oserve_mixed_plan_t* plan, void* workspace, size_t workspace_bytes,
+                                        const void* q, const void* k_pages, const void* v_pages,
+                                        const int32_t* block_table, const int32_t* context_lens, float scale,
+                                        float* out, void* stream);
+/* Optional timing of the mixed kernel, as oserve_plan_enable_timing / oserve_plan_split_kernel_ms. */
+oserve_status_t oserve_mixed_plan_enable_timing(oserve_mixed_plan_t* plan, int32_t enable);
+oserve_status_t oserve_mixed_plan_kernel_ms(oserve_mixed_plan_t* plan, float* mean_ms, int32_t* count);
 
 
 /* ---------------------------------------------------------------------------

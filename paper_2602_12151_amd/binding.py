@@ -74,6 +74,27 @@ def _load() -> ctypes.CDLL:
     lib.oserve_prefill_plan_enable_timing.argtypes = [vp, i32]
     lib.oserve_prefill_plan_kernel_ms.restype = ctypes.c_int
     lib.oserve_prefill_plan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
+    lib.oserve_mixed_plan_create.restype = ctypes.c_int
+    lib.oserve_mixed_plan_create.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i64, ctypes.POINTER(vp)]
+    lib.oserve_mixed_plan_update.restype = ctypes.c_int
+    lib.oserve_mixed_plan_update.argtypes = [vp, vp, vp, i32]
+    lib.oserve_mixed_plan_destroy.restype = None
+    lib.oserve_mixed_plan_destroy.argtypes = [vp]
+    lib.oserve_mixed_plan_query_tokens.restype = i64
+    lib.oserve_mixed_plan_query_tokens.argtypes = [vp]
+    lib.oserve_mixed_plan_counts.restype = ctypes.c_int
+    lib.oserve_mixed_plan_counts.argtypes = [vp, pi32]
+    lib.oserve_mixed_plan_prefill_item.restype = ctypes.c_int
+    lib.oserve_mixed_plan_prefill_item.argtypes = [vp, i32, pi32]
+    for name in ("oserve_mixed_plan_workspace_bytes", "oserve_mixed_plan_workspace_bytes_max"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [vp]
+    lib.oserve_paged_mixed_attn.restype = ctypes.c_int
+    lib.oserve_paged_mixed_attn.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_mixed_plan_enable_timing.restype = ctypes.c_int
+    lib.oserve_mixed_plan_enable_timing.argtypes = [vp, i32]
+    lib.oserve_mixed_plan_kernel_ms.restype = ctypes.c_int
+    lib.oserve_mixed_plan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float), pi32]
     lib.oserve_kv_migration_create.restype = ctypes.c_int
     lib.oserve_kv_migration_create.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(vp)]
     lib.oserve_kv_migration_destroy.restype = None
@@ -364,6 +385,112 @@ def paged_prefill_attn(plan: PrefillPlan, q: torch.Tensor, k_pages: torch.Tensor
                                        ctypes.c_float(scale), _ptr(out), ctypes.c_void_p(s.cuda_stream))
     if st != OK:
         raise OserveError(st, "oserve_paged_prefill_attn")
+    return out
+
+
+class MixedPlan:
+    """Owns an oserve_mixed_plan_t*.  Mirrors oserve_mixed_plan_* one to one."""
+
+    def __init__(self, context_lens_host, q_lens_host, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                 page_size: int, max_pages_per_seq: int, device_id: int = 0, capacity: int | None = None,
+                 max_query_tokens: int | None = None):
+        lens, qlens = _host_lens(context_lens_host), _host_lens(q_lens_host)
+        if lens.shape != qlens.shape:
+            raise ValueError("context_lens_host and q_lens_host must have the same length")
+        self._h = ctypes.c_void_p()
+        self.geometry = (num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq)
+        self.batch = len(lens)
+        st = lib.oserve_mixed_plan_create(lens.ctypes.data, qlens.ctypes.data, len(lens), num_q_heads, num_kv_heads,
+                                          head_dim, page_size, max_pages_per_seq, device_id,
+                                          len(lens) if capacity is None else capacity,
+                                          int(qlens.sum()) if max_query_tokens is None else max_query_tokens,
+                                          ctypes.byref(self._h))
+        if st != OK:
+            self._h = ctypes.c_void_p()
+            raise OserveError(st, "oserve_mixed_plan_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def update(self, context_lens_host, q_lens_host) -> None:
+        lens, qlens = _host_lens(context_lens_host), _host_lens(q_lens_host)
+        st = lib.oserve_mixed_plan_update(self._h, lens.ctypes.data, qlens.ctypes.data, len(lens))
+        if st != OK:
+            raise OserveError(st, "oserve_mixed_plan_update")
+        self.batch = len(lens)
+
+    @property
+    def query_tokens(self) -> int:
+        return lib.oserve_mixed_plan_query_tokens(self._h)
+
+    @property
+    def counts(self) -> dict:
+        c = (ctypes.c_int32 * 4)()
+        st = lib.oserve_mixed_plan_counts(self._h, c)
+        if st != OK:
+            raise OserveError(st, "oserve_mixed_plan_counts")
+        return dict(zip(("workgroups", "prefill_items", "decode_items", "prefill_queues"), list(c)))
+
+    def prefill_item(self, i: int) -> dict:
+        f = (ctypes.c_int32 * 7)()
+        st = lib.oserve_mixed_plan_prefill_item(self._h, i, f)
+        if st != OK:
+            raise OserveError(st, "oserve_mixed_plan_prefill_item")
+        return dict(zip(("queue", "request", "kv_head", "q_begin", "q_row0", "context_len", "q_len"), list(f)))
+
+    @property
+    def workspace_bytes(self) -> int:
+        return lib.oserve_mixed_plan_workspace_bytes(self._h)
+
+    @property
+    def workspace_bytes_max(self) -> int:
+        return lib.oserve_mixed_plan_workspace_bytes_max(self._h)
+
+    def enable_timing(self, enable: bool = True) -> None:
+        st = lib.oserve_mixed_plan_enable_timing(self._h, int(enable))
+        if st != OK:
+            raise OserveError(st, "oserve_mixed_plan_enable_timing")
+
+    def kernel_ms(self):
+        ms, n = ctypes.c_float(), ctypes.c_int32()
+        st = lib.oserve_mixed_plan_kernel_ms(self._h, ctypes.byref(ms), ctypes.byref(n))
+        if st != OK:
+            raise OserveError(st, "oserve_mixed_plan_kernel_ms")
+        return ms.value, n.value
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) and self._h.value and lib is not None:
+            lib.oserve_mixed_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = destroy
+
+
+def paged_mixed_attn(plan: MixedPlan, workspace: torch.Tensor, q: torch.Tensor, k_pages: torch.Tensor,
+                     v_pages: torch.Tensor, block_table: torch.Tensor, context_lens: torch.Tensor, scale: float,
+                     out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_mixed_attn on torch tensors (layout checks only; no arithmetic here)."""
+    tensors = (workspace, q, k_pages, v_pages, block_table, context_lens, out)
+    if not all(t.is_cuda and t.is_contiguous() for t in tensors):
+        raise ValueError("all tensors must be contiguous device tensors")
+    if q.dtype != torch.bfloat16 or k_pages.dtype != torch.bfloat16 or v_pages.dtype != torch.bfloat16:
+        raise TypeError("q / k_pages / v_pages must be bf16")
+    if block_table.dtype != torch.int32 or context_lens.dtype != torch.int32 or out.dtype != torch.float32:
+        raise TypeError("block_table / context_lens must be int32 and out fp32")
+    hq, hkv, d, page, width = plan.geometry
+    if tuple(q.shape) != (plan.query_tokens, hq, d) or out.shape != q.shape:
+        raise ValueError(f"q / out must be [{plan.query_tokens}, {hq}, {d}] for this plan")
+    if k_pages.dim() != 4 or tuple(k_pages.shape[1:]) != (hkv, page, d) or v_pages.shape != k_pages.shape:
+        raise ValueError(f"k_pages / v_pages must be [pages, {hkv}, {page}, {d}] for this plan")
+    if tuple(block_table.shape) != (plan.batch, width) or tuple(context_lens.shape) != (plan.batch,):
+        raise ValueError(f"block_table / context_lens must be [{plan.batch}, {width}] / [{plan.batch}] for this plan")
+    s = torch.cuda.current_stream(q.device) if stream is None else stream
+    st = lib.oserve_paged_mixed_attn(plan.handle, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(context_lens),
+                                     ctypes.c_float(scale), _ptr(out), ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_paged_mixed_attn")
     return out
 
 

@@ -184,6 +184,19 @@ def prefill_workload(which: int):
     return w, lens.astype(np.int32), qlens.astype(np.int32)
 
 
+def mixed_workload():
+    """(Workload, context lengths, query lengths) of the mixed prefill + decode benchmark batch: the 256 decode
+    requests of the heterogeneous mix (one query token each) followed by 8 prefill chunks of 512 tokens that end
+    contexts uniform in [2048, 16384] - one step of a serving engine that runs chunked prefill next to its decodes."""
+    w3 = WORKLOADS[3]
+    dec = context_lens(w3)
+    ctx = CounterRng(BASE_SEED + 200).integers(2048, 16384, 8)
+    lens = np.concatenate([dec, ctx]).astype(np.int32)
+    qlens = np.concatenate([np.ones(len(dec), dtype=np.int64), np.full(8, 512)]).astype(np.int32)
+    w = Workload(200, "mixed-prefill-decode", batch=len(lens), num_q_heads=32, num_kv_heads=8, head_dim=128)
+    return w, lens, qlens
+
+
 def pages_needed(lens: np.ndarray, page_size: int = PAGE_SIZE) -> np.ndarray:
     return (lens.astype(np.int64) + page_size - 1) // page_size
 

@@ -190,3 +190,39 @@ def test_prefill_plan_items_cover_every_query_block_once():
             assert any(len(lane_of_group[g]) == 1 for g in big) or not big
         assert len(seen) == sum(-(-n // qb) for n in qlens) * hkv
         assert plan.query_tokens == sum(qlens)
+
+
+def test_mixed_plan_queues_hold_every_prefill_item_once():
+    """A mixed batch: the requests with one query token become decode work items (the same ones a decode plan
+    over them alone would hold) and get no prefill items; the others become prefill items of 32 query tokens
+    (group of 4 heads) x kv heads, each in exactly one queue, the blocks of one (request, kv head) in one queue."""
+    lens = wl.context_lens(wl.WORKLOADS[3])[:96].copy()
+    qlens = np.ones_like(lens)
+    chunks = [5, 17, 40, 77]
+    for b in chunks:
+        lens[b] = max(lens[b], 700)
+        qlens[b] = min(lens[b], 300 + b)
+    width = int(wl.pages_needed(lens).max())
+    plan = binding.MixedPlan(lens, qlens, 32, 8, 128, 16, width, -1)
+    c = plan.counts
+    qb = 32
+    assert c["prefill_items"] == sum(-(-int(qlens[b]) // qb) for b in chunks) * 8
+    assert c["workgroups"] == 512 and c["prefill_queues"] == 8          # the defaults of a plan without a device
+    rows = np.concatenate([[0], np.cumsum(qlens)])
+    seen, queue_of_group, last_queue = set(), {}, 0
+    for i in range(c["prefill_items"]):
+        it = plan.prefill_item(i)
+        b = it["request"]
+        assert b in chunks and it["q_len"] == qlens[b] and it["context_len"] == lens[b] and it["q_row0"] == rows[b]
+        assert it["q_begin"] % qb == 0 and it["q_begin"] < qlens[b]
+        key = (b, it["kv_head"], it["q_begin"])
+        assert key not in seen
+        seen.add(key)
+        assert queue_of_group.setdefault((b, it["kv_head"]), it["queue"]) == it["queue"]
+        assert it["queue"] >= last_queue                                  # queue after queue
+        last_queue = it["queue"]
+    assert len(seen) == c["prefill_items"] and len(set(queue_of_group.values())) == 8
+    assert plan.query_tokens == int(qlens.sum())
+    assert plan.workspace_bytes <= plan.workspace_bytes_max
+    dec = binding.Plan(lens[qlens == 1], 32, 8, 128, 16, width, 0, -1)
+    assert dec.num_work_items == c["decode_items"]
