@@ -163,6 +163,33 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
                                          float scale, float* out, void* stream);
 
 /*
+ * The same decode step for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Identical to
+ * oserve_paged_decode_attn except that the workspace is a fixed array of
+ * OSERVE_STATIC_WORKSPACE_BYTES bytes that the library holds in the memory of every GPU it is
+ * loaded on, from load until the process ends.  The call itself allocates and frees nothing (no
+ * hipMalloc, no hipFree, no allocating library routine) and enqueues the same three kernels.
+ *
+ *   - A plan whose oserve_plan_workspace_bytes() exceeds OSERVE_STATIC_WORKSPACE_BYTES is refused
+ *     with OSERVE_ERR_WORKSPACE (the heterogeneous-mix benchmark batch needs 11 MB).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *     (different streams, or different threads) race, whatever plans they use.  Calls on one
+ *     stream are ordered and safe.  The array keeps the previous call's contents; nothing in it
+ *     has to be cleared between calls.
+ *   - oserve_static_workspace_init(device) looks up the array's address on `device` ahead of
+ *     time (set-up code; it may load the library's device code).  Without it the first
+ *     oserve_paged_decode_attn_static call on a device does the look-up itself.
+ * Other arguments, errors and undefined behaviour: as oserve_paged_decode_attn.
+ */
+#define OSERVE_STATIC_WORKSPACE_BYTES (32u << 20)
+size_t oserve_static_workspace_bytes(void);
+oserve_status_t oserve_static_workspace_init(int32_t device_id);
+oserve_status_t oserve_paged_decode_attn_static(oserve_plan_t* plan, const void* q, const void* k_pages,
+                                                const void* v_pages, const int32_t* block_table,
+                                                const int32_t* context_lens, float scale, float* out,
+                                                void* stream);
+
+/*
  * Optional timing of the split kernel alone.  When enabled, each launch
  * attaches a begin and an end HIP event to the split kernel's dispatch on the
  * launch stream.

@@ -50,6 +50,12 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).argtypes = [vp]
     lib.oserve_paged_decode_attn.restype = ctypes.c_int
     lib.oserve_paged_decode_attn.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_paged_decode_attn_static.restype = ctypes.c_int
+    lib.oserve_paged_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_static_workspace_bytes.restype = sz
+    lib.oserve_static_workspace_bytes.argtypes = []
+    lib.oserve_static_workspace_init.restype = ctypes.c_int
+    lib.oserve_static_workspace_init.argtypes = [i32]
     lib.oserve_plan_enable_timing.restype = ctypes.c_int
     lib.oserve_plan_enable_timing.argtypes = [vp, i32]
     lib.oserve_plan_split_kernel_ms.restype = ctypes.c_int
@@ -269,6 +275,30 @@ def paged_decode_attn(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pa
                                       ctypes.c_void_p(s.cuda_stream))
     if st != OK:
         raise OserveError(st, "oserve_paged_decode_attn")
+    return out
+
+
+def static_workspace_bytes() -> int:
+    return lib.oserve_static_workspace_bytes()
+
+
+def static_workspace_init(device_id: int = 0) -> None:
+    st = lib.oserve_static_workspace_init(device_id)
+    if st != OK:
+        raise OserveError(st, "oserve_static_workspace_init")
+
+
+def paged_decode_attn_static(plan: Plan, q: torch.Tensor, k_pages: torch.Tensor, v_pages: torch.Tensor,
+                             block_table: torch.Tensor, context_lens: torch.Tensor, scale: float,
+                             out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_decode_attn_static on torch tensors: the decode step on the library's fixed workspace."""
+    _check_decode_tensors(plan, q, k_pages, v_pages, block_table, context_lens, out)
+    s = torch.cuda.current_stream(q.device) if stream is None else stream
+    st = lib.oserve_paged_decode_attn_static(plan.handle, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                             _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
+                                             ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_paged_decode_attn_static")
     return out
 
 
