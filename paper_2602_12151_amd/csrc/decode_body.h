@@ -62,10 +62,7 @@ __device__ __forceinline__ float wave_xor_f32(float v, int mask) { return __shfl
 // kPacked: the request's rows of q and out are found through the request table (a batch in which
 // requests bring different numbers of query rows); otherwise row = request index.
 template <int D, int NBUF, bool kPacked>
-__device__ __forceinline__ void decode_item_body(const SplitParams& p, const int item, int lane) {
-    // opaque per item, so that a caller's loop over items does not keep this function's lane-dependent
-    // constants alive across whatever else the loop does
-    asm volatile("" : "+v"(lane));
+__device__ __forceinline__ void decode_item_body(const SplitParams& p, const int item, const int lane) {
     constexpr int KK = D / 32;  // K fragments (16 B) per lane per page = QK MFMAs per page
     constexpr int EV = D / 16;  // V elements per lane per token = PV MFMA tiles per page
     constexpr int VW = EV / 2;  // 32-bit words of V per lane per token

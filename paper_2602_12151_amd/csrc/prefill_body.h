@@ -93,11 +93,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     lds_byte* const lds_k = lds;              // K tiles: double-buffered
     lds_byte* const lds_v = lds + 2 * TILE;   // V tiles: with eight wavefronts one more, for those that run a macro step late
 
-    // The lane index is made opaque to the compiler per item: a caller that loops over items (the mixed
-    // kernel) would otherwise keep every lane-dependent constant of this function alive in registers
-    // across whatever else its loop does.
-    int lane = threadIdx.x & 63;
-    asm volatile("" : "+v"(lane));
+    const int lane = threadIdx.x & 63;
     const int i16 = lane & 15;
     const int g4 = lane >> 4;
 
