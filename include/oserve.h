@@ -218,10 +218,12 @@ const char* oserve_status_string(oserve_status_t status);
  * decode step; a whole prompt is n_b = L_b.  A batch that holds decode requests
  * next to prefill chunks is served by oserve_paged_mixed_attn below.
  *
- * One workgroup of eight wavefronts handles a block of 256 / G query tokens of one
- * request against one kv head (G = num_q_heads / num_kv_heads); K and V tiles go
- * through LDS; both products run on bf16 MFMA with fp32 accumulation; the
- * probabilities are rounded to bf16 for the second product.
+ * One workgroup of four wavefronts handles a block of 128 / G query tokens of one
+ * request against one kv head (G = num_q_heads / num_kv_heads), two workgroups per
+ * compute unit; K and V tiles go through LDS; both products run on bf16 MFMA with
+ * fp32 accumulation; the probabilities are rounded to bf16 for the second product and
+ * normalised by the sum of the rounded values, so an output row is an exact convex
+ * combination of value rows.
  * Supported shapes: head_dim 128; page_size 16, 32 or 64; G in {1, 2, 4, 8, 16}.
  * ------------------------------------------------------------------------- */
 typedef struct oserve_prefill_plan oserve_prefill_plan_t;

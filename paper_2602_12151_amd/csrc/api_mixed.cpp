@@ -121,7 +121,6 @@ oserve_status_t oserve_mixed_plan_create(const int32_t* context_lens_host, const
     pl->prefill.geo = geo;
     pl->prefill.capacity = capacity;
     pl->prefill.max_query_tokens = max_query_tokens;
-    pl->prefill.waves = oserve::kPrefillNarrowWaves;
     oserve::DeviceFacts facts;
     bool ok = true;
     if (device_id >= 0) {

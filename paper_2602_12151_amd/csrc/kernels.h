@@ -58,12 +58,11 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream);
 
 // ---- chunked prefill (prefill.hip) ----
-constexpr int kPrefillWaves = 8;        // wavefronts per workgroup of the prefill kernel (two per SIMD)
-constexpr int kPrefillNarrowWaves = 4;  // wavefronts that share a prefill item in the mixed kernel (one per SIMD)
+constexpr int kPrefillWaves = 4;        // wavefronts that share a prefill item (one per SIMD; two workgroups per compute unit)
 constexpr int kPrefillColTiles = 2;     // 16-column score tiles per wavefront
 constexpr int kPrefillMacroKeys = 64;   // keys staged in LDS per barrier
-// query tokens of one work item of a workgroup of `waves` wavefronts for a GQA group of 1 << group_shift heads
-inline int prefill_block_tokens(int group_shift, int waves = kPrefillWaves) { return waves * ((16 * kPrefillColTiles) >> group_shift); }
+// query tokens of one work item for a GQA group of 1 << group_shift heads
+inline int prefill_block_tokens(int group_shift) { return kPrefillWaves * ((16 * kPrefillColTiles) >> group_shift); }
 
 // One workgroup's work: a block of query tokens of one request against one kv head.
 struct PrefillItem {

@@ -17,8 +17,7 @@
 // Registers and LDS are budgeted so that a compute unit holds exactly two of them, and the
 // dispatcher places the first workgroup of every compute unit of an XCD before the second; the
 // workgroups that come first are "prefill workgroups", the ones that come second "decode
-// workgroups".  A prefill workgroup works through prefill items (prefill_body.h in its
-// four-wavefront form), all four wavefronts on one item; each wavefront of a decode workgroup works
+// workgroups".  A prefill workgroup works through prefill items (prefill_body.h), all four wavefronts on one item; each wavefront of a decode workgroup works
 // through decode items (decode_body.h) on its own.  Every SIMD thus runs a prefill wavefront's MFMAs
 // next to a decode wavefront's K/V stream for as long as both queues last.  A workgroup whose queue
 // has run dry turns to the other queue, so the tail of the launch is all decode (eight wavefronts per
@@ -36,7 +35,7 @@
 namespace oserve {
 namespace {
 
-constexpr int kMixedWaves = kPrefillNarrowWaves;    // wavefronts of a workgroup
+constexpr int kMixedWaves = kPrefillWaves;         // wavefronts of a workgroup
 constexpr int kMixedThreads = 64 * kMixedWaves;
 
 // The two kinds of work item as functions of their own (not inlined).  Compiled into one function with
@@ -58,7 +57,7 @@ __device__ __attribute__((noinline)) void run_prefill_item(KernelArgs a, int ite
     u.tile_shift = a->prefill.tile_shift;
     // the wavefront index as every lane computes it, not as a value known to be wave-uniform: the prefill code
     // compiles to fewer registers that way
-    prefill_detail::prefill_item_body<D, kMixedWaves>(u, u.items + __builtin_amdgcn_readfirstlane(item), lds,
+    prefill_detail::prefill_item_body<D>(u, u.items + __builtin_amdgcn_readfirstlane(item), lds,
                                                       prefill_detail::WorkgroupBarrier{}, static_cast<int>(threadIdx.x) >> 6);
 }
 
@@ -76,7 +75,7 @@ __device__ __attribute__((noinline)) void run_decode_item(KernelArgs a, int item
 template <int D>
 __global__ __launch_bounds__(kMixedThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void paged_mixed_kernel(const MixedParams p) {
-    __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D, kMixedWaves>()];
+    __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D>()];
     __shared__ int picked[2];             // the prefill item the workgroup takes next (two slots, used in turn)
 
     const int lane = threadIdx.x & 63;

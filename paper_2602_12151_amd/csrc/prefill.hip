@@ -7,10 +7,10 @@ namespace {
 
 template <int D>
 __global__ __launch_bounds__(prefill_detail::kPrefillThreads)
-__attribute__((amdgpu_waves_per_eu(kPrefillWaves / 4, kPrefillWaves / 4)))
+__attribute__((amdgpu_waves_per_eu(2, 2)))   // registers budgeted for two workgroups per compute unit
 void paged_prefill_kernel(const PrefillParams p) {
-    __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D, kPrefillWaves>()];
-    prefill_detail::prefill_item_body<D, kPrefillWaves>(p, p.items + blockIdx.x, (prefill_detail::lds_byte*)lds,
+    __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D>()];
+    prefill_detail::prefill_item_body<D>(p, p.items + blockIdx.x, (prefill_detail::lds_byte*)lds,
                                                         prefill_detail::WorkgroupBarrier{}, static_cast<int>(threadIdx.x) >> 6);
 }
 

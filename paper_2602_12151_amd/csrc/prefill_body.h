@@ -6,22 +6,24 @@
 // of its L_b cached tokens; query token i sits at position p = L_b - n_b + i and attends to the
 // cached tokens 0..p.  n_b = 1 is a decode step.
 //
-// How, on CDNA4: one workgroup of eight wavefronts (two per SIMD, so that one wavefront's MFMAs
-// overlap the other's softmax arithmetic) per (request, kv head, block of query tokens).  Every
-// wavefront owns 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the
-// workgroup's 256 columns share each K/V tile.  Keys advance 32 at a time:
+// How, on CDNA4: one workgroup of four wavefronts, one per SIMD, per (request, kv head, block of
+// query tokens); registers and LDS are budgeted for two workgroups per compute unit, so that every
+// SIMD holds two wavefronts of different workgroups, whose phases drift apart: one's MFMAs then
+// overlap the other's softmax arithmetic.  (Measured against one workgroup of eight wavefronts in
+// which every second wavefront ran its softmax and value phases a macro step late: the same speed on
+// long contexts, 5 % faster on whole prompts, less LDS and no third V buffer.)  Every wavefront owns
+// 32 score columns = (32 / G) query tokens x the G heads of the GQA group, so the workgroup's 128
+// columns share each K/V tile.  Keys advance kMacroKeys at a time:
 //   * the wavefronts bring K and V tiles of kMacroKeys keys from the page pool straight into LDS
-//     (buffer loads with the LDS flag, 16 bytes per lane, no staging registers).  A load instruction fills 1 KB of
-//     LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's row are
-//     stored XOR-swizzled.  A 16-byte-per-lane LDS read is served 16 lanes at a time (measured:
-//     lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, the same in the upper
-//     half), and those 16 must hit 16 different chunk positions of the 256-byte bank row: K chunks
-//     are XOR-ed with the key index (lane l fetches chunk (l % 16) ^ key).  V is read with the
-//     transposing 8-byte read, 32 lanes served together: V chunks are XOR-ed with 2 (key % 8).
-//     One barrier per kMacroKeys keys; the loads of the
-//     next macro step are in flight during the current one;
-//     half of the wavefronts run their softmax and value phases one macro step late, so that on
-//     every SIMD one wavefront's MFMAs overlap the other's softmax arithmetic;
+//     (buffer loads with the LDS flag, 16 bytes per lane, no staging registers).  A load instruction
+//     fills 1 KB of LDS contiguously, so rows cannot be padded; instead the 16-byte chunks of a key's
+//     row are stored XOR-swizzled.  A 16-byte-per-lane LDS read is served 16 lanes at a time
+//     (measured: lanes 0-3, 12-15, 20-23, 24-27 together, 4-11, 16-19, 28-31 together, the same in the
+//     upper half), and those 16 must hit 16 different chunk positions of the 256-byte bank row: K
+//     chunks are XOR-ed with the key index (lane l fetches chunk (l % 16) ^ key).  V is read with the
+//     transposing 8-byte read, 32 lanes served together: V chunks are XOR-ed with 2 (key % 8).  One
+//     barrier per kMacroKeys keys; the loads of the next macro step are in flight during the current
+//     one;
 //   * S^T[key][col] = K_tile * Q^T with 16x16x32 bf16 MFMA (K from LDS as the A operand, Q held in
 //     registers as the B operand for the whole item);
 //   * online softmax in the log2 domain, one update per column and macro step, per-column state
@@ -33,7 +35,10 @@
 //   * O^T[dim][col] += V_tile^T * P^T with 16x16x32 bf16 MFMA over all 32 keys of the step: the
 //     score layout (lane holds keys 4g..4g+3 of each 16-key half) is used as the contraction order,
 //     and the transposing LDS read (ds_read_b64_tr_b16) delivers V^T in exactly that order.
-// Accumulation is fp32; P is rounded to bf16 for the second product.
+//   * the column sums of the weights (the softmax normaliser) come from the matrix cores as well: a
+//     product of the rounded weights with an operand of ones.
+// Accumulation is fp32; P is rounded to bf16 for the second product, and the normaliser is the sum
+// of those rounded weights, so an output row is an exact convex combination of value rows.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
@@ -54,35 +59,27 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float xor_f32(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-constexpr int kPrefillThreads = 64 * kPrefillWaves;            // the prefill kernel's workgroup
-constexpr int kPrefillNarrowThreads = 64 * kPrefillNarrowWaves; // the workgroup of the mixed kernel
+constexpr int kPrefillThreads = 64 * kPrefillWaves;
 constexpr int kColTiles = kPrefillColTiles;
 constexpr int kStepKeys = 32;
 constexpr int kMacroKeys = kPrefillMacroKeys;
 constexpr float kSumLimit = 1048576.f;   // a column's sum of weights over a macro step beyond this moves the reference point of the softmax
 
-// One work item: the whole workgroup (64 * WAVES threads) must call this with the same `ip`.
-// WAVES = 8: two wavefronts per SIMD, the second half of them a macro step late (see above).
-// WAVES = 4: one wavefront per SIMD, all in the same phase order, half the query tokens per item
-// and 64 KB of LDS, so that two such workgroups - or one and a workgroup of other work - share a
-// compute unit.
-// `lds` points to prefill_lds_bytes<D, WAVES>() bytes of LDS that belong to these wavefronts alone;
-// `sync()` is a barrier among exactly these 64 * WAVES threads (the whole workgroup for the prefill
-// kernel, one half of it for the mixed kernel); `wave` is the wavefront's index among them.
+// One work item: the whole workgroup (kPrefillThreads threads: four wavefronts, one per SIMD) must
+// call this with the same `ip`.  `lds` points to prefill_lds_bytes<D>() bytes of LDS;
+// `sync()` is a barrier among these threads; `wave` is the wavefront's index among them.
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
-template <int D, int WAVES>
-constexpr int prefill_lds_bytes() { return (2 + (WAVES == 8 ? 3 : 2)) * kPrefillMacroKeys * D * 2; }
+template <int D>
+constexpr int prefill_lds_bytes() { return 4 * kPrefillMacroKeys * D * 2; }   // K and V tiles, both double-buffered
 
 struct WorkgroupBarrier {
     __device__ __forceinline__ void operator()() const { __syncthreads(); }
 };
 
-template <int D, int WAVES, class Sync>
+template <int D, class Sync>
 __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const PrefillItem* ip, lds_byte* lds,
                                                   const Sync& sync, const int wave) {
-    static_assert(WAVES == 8 || WAVES == 4, "eight or four wavefronts per workgroup");
-    constexpr int NV = WAVES == 8 ? 3 : 2;   // V buffers
     static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
     constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
@@ -91,7 +88,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
     constexpr int CT = kColTiles;
     lds_byte* const lds_k = lds;              // K tiles: double-buffered
-    lds_byte* const lds_v = lds + 2 * TILE;   // V tiles: with eight wavefronts one more, for those that run a macro step late
+    lds_byte* const lds_v = lds + 2 * TILE;   // V tiles: likewise
 
     const int lane = threadIdx.x & 63;
     const int i16 = lane & 15;
@@ -129,7 +126,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     }
     const int pos_min = first_pos + min(tok0, n - 1);             // wave-uniform
     const int pos_max = first_pos + min(tok0 + rt - 1, n - 1);
-    const int blk_last = min(q_begin + WAVES * rt, n) - 1;   // last query token of the block
+    const int blk_last = min(q_begin + kPrefillWaves * rt, n) - 1;   // last query token of the block
     const int num_steps = (first_pos + blk_last) / kStepKeys + 1; // keys 0..pos of that token
 
     // ---- where the 16-token tiles live (same walk as the decode kernel) ----
@@ -140,19 +137,18 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     const int64_t head_off = (static_cast<int64_t>(kvh) * 16 * D) << p.tile_shift;
 
     // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
-    // of 4 KB into LDS.  With eight wavefronts, wavefront w fetches tile w % TILES of K (w < TILES) or
-    // of V; with four, wavefront w fetches tile w of K and tile w of V (two staging slots).  One
+    // of 4 KB into LDS: wavefront w fetches tile w of K and tile w of V (two staging slots).  One
     // quarter of a tile (four keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk
     // (l % 16) ^ key for K and chunk (l % 16) ^ 2 (key % 8) for V. ----
     constexpr int TILES = kMacroKeys / 16;
-    static_assert(2 * TILES == 8, "eight tiles staged per macro step");
-    constexpr int NS = 2 * TILES / WAVES;  // staging slots of a wavefront
-    const int st_tile = wave % TILES;      // the same tile index for all slots of a wavefront: one page id serves them
+    static_assert(TILES == kPrefillWaves, "one K tile and one V tile per wavefront");
+    constexpr int NS = 2;                  // staging slots of a wavefront: its K tile, its V tile
+    const int st_tile = wave;              // the same tile index for both slots: one page id serves them
     bool st_is_v[NS];
     int st_lane_off[NS][4];                // byte offset of this lane's chunk within the tile, per quarter
 #pragma unroll
     for (int sl = 0; sl < NS; ++sl) {
-        st_is_v[sl] = wave + sl * WAVES >= TILES;
+        st_is_v[sl] = sl == 1;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int key = 4 * q + (lane >> 4);
@@ -180,7 +176,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
         next_in_page = (t & tile_mask) * (16 * D);
     };
     auto stage_of = [&](int sl, int macro) -> lds_byte* {   // where this wavefront's tile of macro step `macro` goes
-        return (st_is_v[sl] ? lds_v + (macro % NV) * TILE : lds_k + (macro & 1) * TILE) + st_tile * 16 * ROW;
+        return (st_is_v[sl] ? lds_v : lds_k) + (macro & 1) * TILE + st_tile * 16 * ROW;
     };
     auto pool_of = [&](int sl) -> const uint16_t* { return st_is_v[sl] ? p.v_pages : p.k_pages; };
     // loads of the macro step whose page id was fetched last
@@ -376,12 +372,10 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
         else softmax_and_values(macro, vt, Plain{});
     };
 
-    // ---- main loop: one barrier per macro step.  With eight wavefronts, the two that share a SIMD (w and
-    // w + 4) run out of phase: the late half finishes macro step M-1 (softmax arithmetic, then value
-    // MFMAs) while the early half computes the scores of macro step M (MFMAs, then its softmax), so
-    // that one's VALU phase overlaps the other's MFMA phases.  That is why V has a third LDS buffer.
+    // ---- main loop: one barrier per macro step.  A compute unit holds two workgroups; the two
+    // wavefronts that then share a SIMD belong to different workgroups and drift apart, so that one's
+    // softmax arithmetic overlaps the other's MFMA phases.
     const int num_macro = (num_steps + SUB - 1) / SUB;
-    const bool late = WAVES == 8 && wave >= 4;
     // macro steps with a key visible to this wavefront: 0 .. my_macros-1
     const int my_macros = min(num_macro, pos_max / kMacroKeys + 1);
     // One macro step.  The tile loads it issues land in buffers that nobody reads before the next
@@ -393,15 +387,10 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
                     __attribute__((always_inline)) {
         if (macro + 1 < num_macro) {
             prefetch(0, dst0, pool0);
-            if constexpr (NS == 2) prefetch(1, dst1, pool1);
+            prefetch(1, dst1, pool1);
             fetch_base(macro + 2);     // clamped to the request's last tile
         }
-        if (!late) {
-            if (macro < my_macros) { scores(kt); finish(macro, vt); }
-        } else {
-            if (macro >= 1 && macro - 1 < my_macros) finish(macro - 1, vt);
-            if (macro < my_macros) scores(kt);
-        }
+        if (macro < my_macros) { scores(kt); finish(macro, vt); }
     };
     // A wavefront's tile loads into LDS must have landed before the barrier lets the others read
     // them: the wait for its outstanding vector-memory loads is written out, not left to the compiler.
@@ -412,12 +401,11 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     sync();
     for (int macro = 0; macro < num_macro; ++macro) {
-        step(macro, stage_of(0, macro + 1), pool_of(0), stage_of(NS - 1, macro + 1), pool_of(NS - 1),
-             lds_k + (macro & 1) * TILE, lds_v + ((macro + (late ? 2 : 0)) % NV) * TILE);
+        step(macro, stage_of(0, macro + 1), pool_of(0), stage_of(1, macro + 1), pool_of(1), lds_k + (macro & 1) * TILE,
+             lds_v + (macro & 1) * TILE);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         sync();
     }
-    if (late && num_macro - 1 < my_macros) finish(num_macro - 1, lds_v + ((num_macro - 1) % NV) * TILE);
 
     // ---- write out: lane holds column i16 of each tile, dims 16*e + 4*g4 + r ----
 #pragma unroll

@@ -17,7 +17,6 @@ struct PrefillWorkList {
     Geometry geo{};
     int32_t capacity = 0;            // largest batch
     int64_t max_query_tokens = 0;    // largest sum of query lengths
-    int32_t waves = kPrefillWaves;   // wavefronts of the workgroup that runs an item (sets the query tokens per item)
     int32_t xcds = 8;                // accelerator dies of the device, each with its own L2 (8 without a device)
     int32_t batch = 0;
     int64_t query_tokens = 0;        // sum of the query lengths of all requests of the batch
@@ -34,7 +33,7 @@ struct PrefillWorkList {
         while ((1 << s) < geo.group()) ++s;
         return s;
     }
-    int32_t block_tokens() const { return prefill_block_tokens(group_shift(), waves); }   // query tokens per workgroup
+    int32_t block_tokens() const { return prefill_block_tokens(group_shift()); }   // query tokens per workgroup
     int64_t max_items() const { return (max_query_tokens / block_tokens() + capacity) * geo.num_kv_heads; }
     void reserve();
     // skip_single_token: requests that bring one query token get no items (a mixed batch serves

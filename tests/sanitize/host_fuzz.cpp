@@ -121,7 +121,6 @@ void fuzz_prefill_lists(int rounds) {
         pl.geo = oserve::Geometry{h[0], h[1], 128, 16 << uniform(0, 2), static_cast<int32_t>(uniform(1, 300))};
         pl.capacity = static_cast<int32_t>(uniform(1, 40));
         pl.max_query_tokens = uniform(1, 20000);
-        pl.waves = uniform(0, 1) ? oserve::kPrefillWaves : oserve::kPrefillNarrowWaves;
         pl.xcds = static_cast<int32_t>(uniform(1, oserve::kMaxXcds));
         CHECK(oserve::PrefillWorkList::check_geometry(pl.geo, 1, pl.capacity, pl.max_query_tokens) == OSERVE_OK);
         pl.reserve();

@@ -170,7 +170,7 @@ def test_prefill_plan_items_cover_every_query_block_once():
     for hq, hkv in [(32, 8), (16, 1), (8, 8)]:
         plan = binding.PrefillPlan(lens, qlens, hq, hkv, 128, 16, 129, -1)
         qb = plan.block_tokens
-        assert qb == 256 // (hq // hkv)
+        assert qb == 128 // (hq // hkv)
         seen = set()
         rows = np.concatenate([[0], np.cumsum(qlens)])
         lane_of_group = {}
