@@ -218,13 +218,15 @@ const char* oserve_status_string(oserve_status_t status);
  * decode step; a whole prompt is n_b = L_b.  A batch that holds decode requests
  * next to prefill chunks is served by oserve_paged_mixed_attn below.
  *
- * One workgroup of four wavefronts handles a block of 128 / G query tokens of one
+ * One workgroup of four wavefronts handles a block of 128 / G query tokens (G a power of two) of one
  * request against one kv head (G = num_q_heads / num_kv_heads), two workgroups per
  * compute unit; K and V tiles go through LDS; both products run on bf16 MFMA with
  * fp32 accumulation; the probabilities are rounded to bf16 for the second product and
  * normalised by the sum of the rounded values, so an output row is an exact convex
  * combination of value rows.
- * Supported shapes: head_dim 128; page_size 16, 32 or 64; G in {1, 2, 4, 8, 16}.
+ * Supported shapes: head_dim 64 or 128; page_size 16, 32 or 64; G <= 16 (a group size that is not a
+ * power of two is padded to the next one: the block then holds 128 / 2^ceil(log2 G) query tokens
+ * and the padding columns are computed and dropped).
  * ------------------------------------------------------------------------- */
 typedef struct oserve_prefill_plan oserve_prefill_plan_t;
 
@@ -297,7 +299,7 @@ oserve_status_t oserve_prefill_plan_kernel_ms(oserve_prefill_plan_t* plan, float
  * the one work through a queue of prefill items together, those of the other each through
  * a queue of decode items, so that every SIMD runs a prefill wavefront's MFMAs next to a
  * decode wavefront's K/V stream.  When one queue runs dry its workgroups turn to the other.
- * Supported shapes: as oserve_paged_prefill_attn (head_dim 128; G in {1, 2, 4, 8, 16}).
+ * Supported shapes: as oserve_paged_prefill_attn (head_dim 64 or 128; G <= 16).
  * ------------------------------------------------------------------------- */
 typedef struct oserve_mixed_plan oserve_mixed_plan_t;
 

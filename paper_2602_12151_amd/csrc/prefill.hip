@@ -19,9 +19,14 @@ void paged_prefill_kernel(const PrefillParams p) {
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
                           hipEvent_t start, hipEvent_t stop) {
     if (num_items <= 0) return hipSuccess;
-    if (head_dim != 128) return hipErrorInvalidValue;
-    hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
-                          start, stop, 0, p);
+    if (head_dim == 128)
+        hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
+                              start, stop, 0, p);
+    else if (head_dim == 64)
+        hipExtLaunchKernelGGL((paged_prefill_kernel<64>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
+                              start, stop, 0, p);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -80,10 +80,10 @@ struct WorkgroupBarrier {
 template <int D, class Sync>
 __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const PrefillItem* ip, lds_byte* lds,
                                                   const Sync& sync, const int wave) {
-    static_assert(D == 128, "the LDS tiling below is written for head_dim 128");
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     constexpr int KK = D / 32;           // 16-byte K fragments per lane per 16-key half = score MFMAs per column tile
     constexpr int EV = D / 16;           // V elements per lane per key = value MFMA row tiles
-    constexpr int ROW = D * 2;           // bytes of one key's row in LDS; chunk c of key k sits at slot c ^ (k % 16)
+    constexpr int ROW = D * 2;           // bytes of one key's row in LDS; chunk c of key k sits at slot c ^ (k % CH) (K) or c ^ 2 (k % (CH / 2)) (V)
     constexpr int TILE = kMacroKeys * ROW;
     constexpr int SUB = kMacroKeys / kStepKeys;   // 32-key steps per macro step
     constexpr int CT = kColTiles;
@@ -108,8 +108,9 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     const int rt = (16 * CT) >> gshift;               // query tokens per wavefront
     const int tok0 = q_begin + wave * rt;             // this wavefront's first query token
     const int first_pos = L - n;                      // position of the request's query 0
-    // columns c = 16*ct + i16  ->  token tok0 + (c >> gshift), head c & (G-1); tokens past the
-    // request's last one are computed as copies of it and not stored
+    // columns c = 16*ct + i16  ->  token tok0 + (c >> gshift), head c & (2^gshift - 1), where 2^gshift
+    // is the group size rounded up to a power of two; tokens past the request's last one and heads
+    // past the group's last one are computed as copies of the last one and not stored
     int tok[CT], pos[CT];
     bf16x8 qf[CT][KK];
 #pragma unroll
@@ -118,7 +119,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
         tok[ct] = tok0 + (c >> gshift);
         const int t_eff = min(tok[ct], n - 1);
         pos[ct] = first_pos + t_eff;
-        const int head = kvh * p.group + (c & (p.group - 1));
+        const int head = kvh * p.group + min(c & ((1 << gshift) - 1), p.group - 1);
         const uint16_t* qrow = p.q + (static_cast<int64_t>(q_row0 + t_eff) * p.num_q_heads + head) * D;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
@@ -137,32 +138,36 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     const int64_t head_off = (static_cast<int64_t>(kvh) * 16 * D) << p.tile_shift;
 
     // ---- staging: per macro step the workgroup brings kMacroKeys / 16 K tiles and as many V tiles
-    // of 4 KB into LDS: wavefront w fetches tile w of K and tile w of V (two staging slots).  One
-    // quarter of a tile (four keys = 1 KB) per load instruction; lane l fetches key 4 q + l / 16, chunk
-    // (l % 16) ^ key for K and chunk (l % 16) ^ 2 (key % 8) for V. ----
+    // (16 keys each) into LDS: wavefront w fetches tile w of K and tile w of V (two staging slots).
+    // A load instruction brings 1 KB = KPL keys (four at head_dim 128, eight at 64); a key's row has
+    // CH 16-byte chunks; lane l fetches key KPL q + l / CH, and of it the chunk that belongs at slot
+    // l % CH of the row: chunk (l % CH) ^ (key % CH) for K and (l % CH) ^ 2 (key % (CH / 2)) for V. ----
+    constexpr int CH = D / 8;              // 16-byte chunks of a row
+    constexpr int KPL = 64 / CH;           // keys per load instruction
+    constexpr int LOADS = 16 / KPL;        // load instructions per tile
     constexpr int TILES = kMacroKeys / 16;
     static_assert(TILES == kPrefillWaves, "one K tile and one V tile per wavefront");
     constexpr int NS = 2;                  // staging slots of a wavefront: its K tile, its V tile
     const int st_tile = wave;              // the same tile index for both slots: one page id serves them
     bool st_is_v[NS];
-    int st_lane_off[NS][4];                // byte offset of this lane's chunk within the tile, per quarter
+    int st_lane_off[NS][LOADS];            // byte offset of this lane's chunk within the tile, per load
 #pragma unroll
     for (int sl = 0; sl < NS; ++sl) {
         st_is_v[sl] = sl == 1;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int key = 4 * q + (lane >> 4);
-            st_lane_off[sl][q] = (key * D + (((lane & 15) ^ (st_is_v[sl] ? 2 * (key & 7) : key)) * 8)) * 2;
+        for (int q = 0; q < LOADS; ++q) {
+            const int key = KPL * q + lane / CH;
+            st_lane_off[sl][q] = (key * D + (((lane % CH) ^ (st_is_v[sl] ? 2 * (key % (CH / 2)) : key % CH)) * 8)) * 2;
         }
     }
     // V is read back with the transposing 8-byte LDS read: in each group of 16 lanes, lane s supplies
     // the address of four consecutive dims (4 (s % 4) ..) of key 4 g4 + s / 4, and lane i receives dim i
-    // of the four keys.  The 16-byte chunks of a V row are stored XOR-ed with 2 (key % 8), which spreads
-    // the 32 lanes served together over all banks.
+    // of the four keys.  The 16-byte chunks of a V row are stored XOR-ed with 2 (key % (CH / 2)), which at
+    // head_dim 128 spreads the 32 lanes served together over all banks.
     int v_off[EV];
     {
         const int key = 4 * g4 + (i16 >> 2);
-        const int t = ((i16 & 3) >> 1) ^ (2 * (key & 7));
+        const int t = ((i16 & 3) >> 1) ^ (2 * (key % (CH / 2)));
 #pragma unroll
         for (int e = 0; e < EV; ++e) v_off[e] = key * ROW + ((2 * e) ^ t) * 16 + (i16 & 1) * 8;
     }
@@ -193,8 +198,8 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
             reinterpret_cast<void*>((static_cast<uintptr_t>(hi) << 32) | lo), 0, 16 * ROW, 0x00020000);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(dst + q * 4 * ROW),
+        for (int q = 0; q < LOADS; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(dst + q * KPL * ROW),
                                                      16, st_lane_off[sl][q], 0, 0, 0);
     };
 
@@ -222,7 +227,7 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
 #pragma unroll
                 for (int kk = 0; kk < KK; ++kk)
                     kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) uint4*>(
-                        kt + (32 * sub + 16 * h + i16) * ROW + (((4 * kk + g4) ^ i16) * 16)));
+                        kt + (32 * sub + 16 * h + i16) * ROW + (((4 * kk + g4) ^ (i16 % CH)) * 16)));
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
                     f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -412,8 +417,9 @@ __device__ __forceinline__ void prefill_item_body(const PrefillParams& p, const 
     for (int ct = 0; ct < CT; ++ct) {
         const float l_tot = l[ct];   // every lane holds its column's whole sum
         const int c = 16 * ct + i16;
-        if (tok[ct] < n) {
-            const int head = kvh * p.group + (c & (p.group - 1));
+        const int head_in_group = c & ((1 << gshift) - 1);
+        if (tok[ct] < n && head_in_group < p.group) {
+            const int head = kvh * p.group + head_in_group;
             float* dst = p.out + (static_cast<int64_t>(q_row0 + tok[ct]) * p.num_q_heads + head) * D + 4 * g4;
             const float inv = 1.f / l_tot;
 #pragma unroll

@@ -10,8 +10,8 @@ oserve_status_t PrefillWorkList::check_geometry(const Geometry& g, int32_t batch
                                                 int64_t max_query_tokens) {
     const oserve_status_t st = SplitPlan::check_geometry(g, batch, capacity, 0);
     if (st != OSERVE_OK) return st;
-    const int32_t grp = g.group();
-    if (g.head_dim != 128 || (grp & (grp - 1)) != 0) return OSERVE_ERR_SHAPE;   // group 1, 2, 4, 8 or 16
+    // (head_dim 64 or 128 and any group size up to 16, which the kernel pads to a power of two: what the
+    // decode plan accepts)
     if (max_query_tokens < 1 || max_query_tokens > (1ll << 28)) return OSERVE_ERR_SHAPE;
     return OSERVE_OK;
 }

@@ -114,11 +114,11 @@ void fuzz_split_plans(int rounds) {
 }
 
 void fuzz_prefill_lists(int rounds) {
-    static const int32_t heads[][2] = {{32, 8}, {16, 2}, {8, 8}, {16, 1}, {4, 2}};
+    static const int32_t heads[][2] = {{32, 8}, {16, 2}, {8, 8}, {16, 1}, {4, 2}, {12, 4}, {6, 2}, {14, 2}};
     for (int it = 0; it < rounds; ++it) {
-        const int32_t* h = heads[uniform(0, 4)];
+        const int32_t* h = heads[uniform(0, 7)];
         oserve::PrefillWorkList pl;
-        pl.geo = oserve::Geometry{h[0], h[1], 128, 16 << uniform(0, 2), static_cast<int32_t>(uniform(1, 300))};
+        pl.geo = oserve::Geometry{h[0], h[1], uniform(0, 1) ? 128 : 64, 16 << uniform(0, 2), static_cast<int32_t>(uniform(1, 300))};
         pl.capacity = static_cast<int32_t>(uniform(1, 40));
         pl.max_query_tokens = uniform(1, 20000);
         pl.xcds = static_cast<int32_t>(uniform(1, oserve::kMaxXcds));

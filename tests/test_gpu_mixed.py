@@ -14,13 +14,13 @@ from tests import gpu_helpers as gh
 pytestmark = pytest.mark.gpu
 
 
-def make_case(lens, qlens, hq=32, hkv=8, page_size=16, seed=0, poison=False):
+def make_case(lens, qlens, hq=32, hkv=8, page_size=16, seed=0, poison=False, head_dim=128):
     lens = np.asarray(lens, dtype=np.int32)
     qlens = np.asarray(qlens, dtype=np.int32)
-    w = wl.Workload(9, "mixed", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=128, page_size=page_size)
+    w = wl.Workload(9, "mixed", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=head_dim, page_size=page_size)
     cpu = wl.make_inputs(w, device="cpu", seed=seed, lens=lens)
     g = torch.Generator().manual_seed(seed + 4242)
-    q = torch.randn(int(qlens.sum()), hq, 128, generator=g).to(torch.bfloat16)
+    q = torch.randn(int(qlens.sum()), hq, head_dim, generator=g).to(torch.bfloat16)
     if poison:   # NaN in every slot past a request's context, and in every page no request owns
         used = np.zeros(cpu.k_pages.shape[0], dtype=bool)
         used[cpu.used_pages] = True
@@ -67,7 +67,7 @@ def check_rows(out, ref, qlens, what):
     return err, parts
 
 
-@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (16, 1)])
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (16, 1), (9, 3), (14, 2)])
 def test_batch_with_both_kinds(hq, hkv):
     """Decode requests (short, long enough to be split, ragged last pages) next to whole prompts and chunks."""
     lens = [1, 17, 300, 5000, 1000, 64, 65, 2049, 513, 9000, 33, 700]
@@ -89,6 +89,14 @@ def test_only_decode_requests_and_only_chunks():
         assert (c["prefill_items"] == 0) == all(n == 1 for n in qlens)
         assert (c["decode_items"] == 0) == all(n > 1 for n in qlens)
         check_rows(out, reference(*case), case[4], f"mixed qlens={qlens}")
+
+
+def test_head_dim_64():
+    lens = [1, 17, 300, 5000, 1000, 64, 65, 2049, 513, 33]
+    qlens = [1, 17, 1, 1, 64, 1, 1, 100, 257, 1]
+    case = make_case(lens, qlens, 8, 2, seed=640, poison=True, head_dim=64)
+    out, _ = run_gpu(*case)
+    check_rows(out, reference(*case), case[4], "mixed head_dim 64")
 
 
 @pytest.mark.parametrize("page_size", [32, 64])
@@ -138,7 +146,7 @@ def test_plan_errors():
         binding.MixedPlan([10], [11], 32, 8, 128, 16, 4, 0)          # n > L
     assert e.value.status == binding.ERR_CONTEXT_LEN
     with pytest.raises(binding.OserveError) as e:
-        binding.MixedPlan([10], [4], 24, 8, 128, 16, 4, 0)           # group 3
+        binding.MixedPlan([10], [4], 34, 2, 128, 16, 4, 0)           # group 17
     assert e.value.status == binding.ERR_SHAPE
     plan = binding.MixedPlan([100, 50], [10, 1], 32, 8, 128, 16, 8, 0, max_query_tokens=16)
     before = plan.counts

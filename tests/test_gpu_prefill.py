@@ -14,13 +14,13 @@ from tests import gpu_helpers as gh
 pytestmark = pytest.mark.gpu
 
 
-def make_case(lens, qlens, hq=32, hkv=8, page_size=16, seed=0, poison=False):
+def make_case(lens, qlens, hq=32, hkv=8, page_size=16, seed=0, poison=False, head_dim=128):
     lens = np.asarray(lens, dtype=np.int32)
     qlens = np.asarray(qlens, dtype=np.int32)
-    w = wl.Workload(9, "prefill", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=128, page_size=page_size)
+    w = wl.Workload(9, "prefill", batch=len(lens), num_q_heads=hq, num_kv_heads=hkv, head_dim=head_dim, page_size=page_size)
     cpu = wl.make_inputs(w, device="cpu", seed=seed, lens=lens)
     g = torch.Generator().manual_seed(seed + 12345)
-    q = torch.randn(int(qlens.sum()), hq, 128, generator=g).to(torch.bfloat16)
+    q = torch.randn(int(qlens.sum()), hq, head_dim, generator=g).to(torch.bfloat16)
     if poison:   # NaN in every slot past a request's context, and in every page no request owns
         used = np.zeros(cpu.k_pages.shape[0], dtype=bool)
         used[cpu.used_pages] = True
@@ -49,7 +49,7 @@ def reference(w, cpu, q, lens, qlens):
     return oracle.paged_prefill_attn(q, cpu.k_pages, cpu.v_pages, cpu.block_table.numpy(), lens, qlens, w.scale)
 
 
-@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (4, 2), (16, 1)])
+@pytest.mark.parametrize("hq,hkv", [(32, 8), (16, 2), (8, 8), (4, 2), (16, 1), (6, 2), (10, 2), (12, 2), (7, 1), (15, 1)])
 def test_mixed_chunks_all_group_sizes(hq, hkv):
     """Whole prompts, chunks at the end of longer contexts, single decode tokens, ragged last blocks."""
     lens = [1, 17, 300, 300, 1000, 64, 65, 2049, 513]
@@ -59,6 +59,16 @@ def test_mixed_chunks_all_group_sizes(hq, hkv):
     assert plan.query_tokens == sum(qlens)
     print(f"hq={hq} hkv={hkv}:", gh.assert_parity(out, reference(*case), f"prefill hq={hq} hkv={hkv}"),
           "items", plan.num_work_items, "block", plan.block_tokens)
+
+
+@pytest.mark.parametrize("hq,hkv,page_size", [(8, 2, 16), (32, 8, 16), (6, 6, 32), (12, 4, 64), (16, 1, 16)])
+def test_head_dim_64(hq, hkv, page_size):
+    lens = [1, 17, 300, 300, 1000, 64, 65, 2049, 513]
+    qlens = [1, 17, 300, 37, 64, 64, 1, 100, 257]
+    case = make_case(lens, qlens, hq, hkv, page_size=page_size, seed=64 + hq, poison=True, head_dim=64)
+    out, plan = run_gpu(*case)
+    print(f"head_dim 64, hq={hq} hkv={hkv} page={page_size}:", gh.assert_parity(out, reference(*case), "prefill head_dim 64"),
+          "items", plan.num_work_items)
 
 
 @pytest.mark.parametrize("page_size", [32, 64])
@@ -104,10 +114,10 @@ def test_plan_errors():
         binding.PrefillPlan([10], [11], 32, 8, 128, 16, 4, 0)          # n > L
     assert e.value.status == binding.ERR_CONTEXT_LEN
     with pytest.raises(binding.OserveError) as e:
-        binding.PrefillPlan([10], [4], 24, 8, 128, 16, 4, 0)           # group 3
+        binding.PrefillPlan([10], [4], 34, 2, 128, 16, 4, 0)           # group 17
     assert e.value.status == binding.ERR_SHAPE
     with pytest.raises(binding.OserveError) as e:
-        binding.PrefillPlan([10], [4], 32, 8, 64, 16, 4, 0)            # head_dim 64
+        binding.PrefillPlan([10], [4], 32, 8, 96, 16, 4, 0)            # head_dim 96
     assert e.value.status == binding.ERR_SHAPE
     plan = binding.PrefillPlan([100], [10], 32, 8, 128, 16, 8, 0, max_query_tokens=16)
     with pytest.raises(binding.OserveError) as e:

@@ -167,10 +167,11 @@ def test_library_exports_every_declared_symbol():
 def test_prefill_plan_items_cover_every_query_block_once():
     lens = [1, 17, 300, 1000, 2049]
     qlens = [1, 17, 37, 1000, 100]
-    for hq, hkv in [(32, 8), (16, 1), (8, 8)]:
+    for hq, hkv in [(32, 8), (16, 1), (8, 8), (12, 4), (14, 2)]:
         plan = binding.PrefillPlan(lens, qlens, hq, hkv, 128, 16, 129, -1)
         qb = plan.block_tokens
-        assert qb == 128 // (hq // hkv)
+        padded = 1 << (hq // hkv - 1).bit_length()          # group size rounded up to a power of two
+        assert qb == 128 // padded
         seen = set()
         rows = np.concatenate([[0], np.cumsum(qlens)])
         lane_of_group = {}
