@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # prints it: it is reported only while the kernel and planner sources still hash to what they were when the
 # profile was taken and the plan has the same number of work items; otherwise `traffic` is null.
 RECORDED_TRAFFIC = {"config": 3, "bytes": round(3_396_606.6 * 2048 + 10_499.5 * 1024), "work_items": 5192,
-                    "sources_sha16": "0174cfa59a0f5fd1", "profile": "profiles/split_kernel_cfg3_heterogeneous_mix.md"}
+                    "sources_sha16": "15d51c11ca338beb", "profile": "profiles/split_kernel_cfg3_heterogeneous_mix.md"}
 
 
 def parse_args():
@@ -378,7 +378,7 @@ def sources_sha16():
     import hashlib
     h = hashlib.sha256()
     root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2602_12151_amd", "csrc")
-    for name in ("kernels.hip", "kernels.h", "plan.cpp", "plan.h"):
+    for name in ("kernels.hip", "decode_body.h", "kernels.h", "plan.cpp", "plan.h"):
         with open(os.path.join(root, name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]

@@ -17,8 +17,9 @@
 // Registers and LDS are budgeted so that a compute unit holds exactly two of them, and the
 // dispatcher places the first workgroup of every compute unit of an XCD before the second; the
 // workgroups that come first are "prefill workgroups", the ones that come second "decode
-// workgroups".  A prefill workgroup works through prefill items (prefill_body.h), all four wavefronts on one item; each wavefront of a decode workgroup works
-// through decode items (decode_body.h) on its own.  Every SIMD thus runs a prefill wavefront's MFMAs
+// workgroups".  A prefill workgroup works through prefill items (prefill_body.h), all four
+// wavefronts on one item; each wavefront of a decode workgroup works through decode items
+// (decode_body.h) on its own.  Every SIMD thus runs a prefill wavefront's MFMAs
 // next to a decode wavefront's K/V stream for as long as both queues last.  A workgroup whose queue
 // has run dry turns to the other queue, so the tail of the launch is all decode (eight wavefronts per
 // compute unit) or all prefill (two items per compute unit).  Should the dispatcher place workgroups
@@ -38,38 +39,76 @@ namespace {
 constexpr int kMixedWaves = kPrefillWaves;         // wavefronts of a workgroup
 constexpr int kMixedThreads = 64 * kMixedWaves;
 
-// The two kinds of work item as functions of their own (not inlined).  Compiled into one function with
-// the queue loops around them, each kind's register pressure spoils the other's instruction schedule
+// The two kinds of work as functions of their own (not inlined), each with its queue loop inside.
+// Compiled into one function, each kind's register pressure spoils the other's instruction schedule
 // (the prefill code loses its software pipelining: every LDS read waits for the one before); as
-// functions each is compiled like the kernel it also exists as.  They read their parameters from the
-// kernel-argument segment, in the constant address space: scalar loads into scalar registers, as in
-// a kernel.  (Handed over by reference the parameters would be vector-memory loads where they are
-// used, and waiting for one of those also waits for every tile or page load in flight.)
+// functions each is compiled like the kernel it also exists as.  The loop over a queue's items is
+// inside the function because a function saves the registers it must preserve to scratch memory on
+// entry and reloads them on exit: per item that was 128 MB of writes per launch and 3 % of its time.
+// The functions read their parameters from the kernel-argument segment, in the constant address
+// space: scalar loads into scalar registers, as in a kernel.  (Handed over by reference the
+// parameters would be vector-memory loads where they are used, and waiting for one of those also
+// waits for every tile or page load in flight.)
 typedef const __attribute__((address_space(4))) MixedParams* KernelArgs;
+typedef __attribute__((address_space(3))) int* LdsInts;
 
+// Next prefill item for the workgroup (the same value in all of its wavefronts), or -1 when every queue is
+// empty.  Its own XCD's queue first, then the others in turn.
+__device__ inline int take_prefill(KernelArgs a, int xcd, LdsInts picked, int& turn) {
+    if (threadIdx.x == 0) {
+        int item = -1;
+        const int nx = a->num_xcds;
+        for (int k = 0; k < nx && item < 0; ++k) {
+            const int x = (xcd + k) % nx;
+            const int n = a->prefill_queue_size[x];
+            if (n == 0) continue;
+            const int i = atomicAdd(a->queue_next + x, 1);
+            if (i < n) item = a->prefill_queue_first[x] + i;
+        }
+        picked[turn] = item;
+    }
+    __syncthreads();
+    const int item = picked[turn];
+    turn ^= 1;                        // the slot is written again only after another barrier
+    return __builtin_amdgcn_readfirstlane(item);
+}
+
+// All four wavefronts of the workgroup on one prefill item after the other, until the queues are empty.
 template <int D>
-__device__ __attribute__((noinline)) void run_prefill_item(KernelArgs a, int item, prefill_detail::lds_byte* lds) {
+__device__ __attribute__((noinline)) void run_prefill_items(KernelArgs a, int xcd, prefill_detail::lds_byte* lds, LdsInts picked) {
     PrefillParams u;
     u.items = a->prefill.items; u.q = a->prefill.q; u.k_pages = a->prefill.k_pages; u.v_pages = a->prefill.v_pages;
     u.block_table = a->prefill.block_table; u.out = a->prefill.out; u.scale_log2e = a->prefill.scale_log2e;
     u.num_q_heads = a->prefill.num_q_heads; u.num_kv_heads = a->prefill.num_kv_heads; u.group = a->prefill.group;
     u.group_shift = a->prefill.group_shift; u.max_pages_per_seq = a->prefill.max_pages_per_seq;
     u.tile_shift = a->prefill.tile_shift;
-    // the wavefront index as every lane computes it, not as a value known to be wave-uniform: the prefill code
-    // compiles to fewer registers that way
-    prefill_detail::prefill_item_body<D>(u, u.items + __builtin_amdgcn_readfirstlane(item), lds,
-                                                      prefill_detail::WorkgroupBarrier{}, static_cast<int>(threadIdx.x) >> 6);
+    int turn = 0;
+#pragma nounroll
+    for (int item = take_prefill(a, xcd, picked, turn); item >= 0; item = take_prefill(a, xcd, picked, turn))
+        prefill_detail::prefill_item_body<D>(u, u.items + item, lds, prefill_detail::WorkgroupBarrier{},
+                                             static_cast<int>(threadIdx.x) >> 6);
 }
 
+// Each wavefront on its own, one decode item after the other, until the queue is empty.
 template <int D>
-__device__ __attribute__((noinline)) void run_decode_item(KernelArgs a, int item) {
+__device__ __attribute__((noinline)) void run_decode_items(KernelArgs a) {
     SplitParams u;
     u.items = a->decode.items; u.req_info = a->decode.req_info; u.q = a->decode.q; u.k_pages = a->decode.k_pages;
     u.v_pages = a->decode.v_pages; u.block_table = a->decode.block_table; u.context_lens = a->decode.context_lens;
     u.out = a->decode.out; u.partial_o = a->decode.partial_o; u.partial_ml = a->decode.partial_ml;
     u.scale_log2e = a->decode.scale_log2e; u.num_q_heads = a->decode.num_q_heads; u.num_kv_heads = a->decode.num_kv_heads;
     u.group = a->decode.group; u.max_pages_per_seq = a->decode.max_pages_per_seq; u.tile_shift = a->decode.tile_shift;
-    decode_detail::decode_item_body<D, 2, true>(u, __builtin_amdgcn_readfirstlane(item), threadIdx.x & 63);
+    const int lane = threadIdx.x & 63;
+    const int n = a->num_decode_items;
+    int32_t* next = a->queue_next + kMaxQueueXcds;
+#pragma nounroll
+    for (;;) {
+        int item = 0;
+        if (lane == 0) item = atomicAdd(next, 1);
+        item = __builtin_amdgcn_readfirstlane(item);
+        if (item >= n) break;
+        decode_detail::decode_item_body<D, 2, true>(u, item, lane);
+    }
 }
 
 template <int D>
@@ -78,7 +117,6 @@ void paged_mixed_kernel(const MixedParams p) {
     __shared__ __align__(16) unsigned char lds[prefill_detail::prefill_lds_bytes<D>()];
     __shared__ int picked[2];             // the prefill item the workgroup takes next (two slots, used in turn)
 
-    const int lane = threadIdx.x & 63;
     // MixedParams is the kernel's only argument, so it sits at the start of the kernel-argument segment
     const KernelArgs args = (KernelArgs)__builtin_amdgcn_kernarg_segment_ptr();
     // Workgroups go to the XCDs in turn; inside an XCD the first units_per_xcd of them are the first
@@ -86,51 +124,19 @@ void paged_mixed_kernel(const MixedParams p) {
     const int xcd = blockIdx.x % p.num_xcds;
     const int units_per_xcd = max(1, static_cast<int>(gridDim.x) / (2 * p.num_xcds));
     const bool prefill_first = ((blockIdx.x / p.num_xcds) / units_per_xcd) % 2 == 0;
-    int turn = 0;
-
-    // Next prefill item for this workgroup (the same value in all of its wavefronts), or -1 when every
-    // queue is empty.  Its own XCD's queue first, then the others in turn.
-    auto take_prefill = [&]() -> int {
-        if (threadIdx.x == 0) {
-            int item = -1;
-            for (int k = 0; k < p.num_xcds && item < 0; ++k) {
-                const int x = (xcd + k) % p.num_xcds;
-                const int n = p.prefill_queue_size[x];
-                if (n == 0) continue;
-                const int i = atomicAdd(p.queue_next + x, 1);
-                if (i < n) item = p.prefill_queue_first[x] + i;
-            }
-            picked[turn] = item;
-        }
-        __syncthreads();
-        const int item = picked[turn];
-        turn ^= 1;                        // the slot is written again only after another barrier
-        return __builtin_amdgcn_readfirstlane(item);
-    };
-    // All four wavefronts on one item.
-    auto prefill_mode = [&]() {
-        __builtin_amdgcn_s_setprio(0);
-        for (int item = take_prefill(); item >= 0; item = take_prefill())
-            run_prefill_item<D>(args, item, (prefill_detail::lds_byte*)lds);
-    };
-    // Every wavefront on its own.  Decode wavefronts issue few instructions and every delay of
-    // theirs is a gap in the K/V stream, so they get the higher issue priority.
-    auto decode_mode = [&]() {
-        __builtin_amdgcn_s_setprio(2);
-        for (;;) {
-            int item = 0;
-            if (lane == 0) item = atomicAdd(p.queue_next + kMaxQueueXcds, 1);
-            item = __builtin_amdgcn_readfirstlane(item);
-            if (item >= p.num_decode_items) break;
-            run_decode_item<D>(args, item);
-        }
-    };
     // a prefill workgroup: prefill queues first, then the decode queue; a decode workgroup the other way
     // round (the first barrier of its prefill phase waits until all four wavefronts have left the decode queue)
 #pragma nounroll
     for (int phase = 0; phase < 2; ++phase) {
-        if ((phase == 0) == prefill_first) prefill_mode();
-        else decode_mode();
+        if ((phase == 0) == prefill_first) {
+            __builtin_amdgcn_s_setprio(0);
+            run_prefill_items<D>(args, xcd, (prefill_detail::lds_byte*)lds, (LdsInts)picked);
+        } else {
+            // Decode wavefronts issue few instructions and every delay of theirs is a gap in the K/V
+            // stream, so they get the higher issue priority.
+            __builtin_amdgcn_s_setprio(2);
+            run_decode_items<D>(args);
+        }
     }
 }
 
