@@ -43,3 +43,19 @@ def test_bench_settling_phase_terminates_and_reports():
     t0 = time.perf_counter()
     seconds, steps = bench.settle(lambda i: time.sleep(0.002), fake_torch, 0.5)
     assert 0.5 <= seconds < 2.0 and steps > 10 and time.perf_counter() - t0 < 3.0
+
+
+def test_recorded_traffic_belongs_to_the_current_sources():
+    """bench.py reports the split kernel's recorded HBM traffic only while the decode sources are the ones it was
+    measured on; this fails when they change, until the profile is taken again and the record renewed."""
+    import importlib
+    bench = importlib.import_module("bench")
+    rec = bench.RECORDED_TRAFFIC
+    assert rec["sources_sha16"] == bench.sources_sha16(), (
+        "decode sources changed since " + rec["profile"] + " was taken: profile again and renew RECORDED_TRAFFIC")
+    assert os.path.exists(os.path.join(ROOT, rec["profile"]))
+    # traffic cannot be below the algorithmic bytes of the workload it was measured on, nor far above
+    from paper_2602_12151_amd import workloads as wl
+    w = wl.WORKLOADS[rec["config"]]
+    algorithmic = wl.kv_bytes(wl.context_lens(w), w.num_kv_heads, w.head_dim)
+    assert algorithmic <= rec["bytes"] <= 1.05 * algorithmic
