@@ -421,6 +421,10 @@ def bench_decode(args, torch, binding, wl, config, with_cpu):
         evs[i + 1].record()
     torch.cuda.synchronize()
     singles = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n_single))
+    # one layer of a model whose layers share the step's plan: descriptors staged once, then split + merge only
+    for j, op in enumerate(ops):
+        op.stage(sets[j])
+    layer_ms, _ = timed_block(lambda i: ops[i % len(sets)].layer(sets[i % len(sets)]), args.steps, torch)
     # the host re-plan alone
     lens_host = sets[0].context_lens_host
     n_plan = 200
@@ -454,6 +458,8 @@ def bench_decode(args, torch, binding, wl, config, with_cpu):
                    "input_copies_rotated": len(sets), "gpu_event_ms_per_step": round(gpu_ms_per_step, 5),
                    "single_step_us_median": round(singles[len(singles) // 2] * 1e3, 2),
                    "single_step_us_min": round(singles[0] * 1e3, 2),
+                   "us_per_layer_plan_staged_once": round(layer_ms * 1e3, 2),
+                   "pct_hbm_peak_per_layer_plan_staged_once": round(100.0 * nbytes / (layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
                    "host_plan_update_us": round(plan_us, 2),
                    "device": f"{prop.name}, {prop.multi_processor_count} CUs, "
                              f"{prop.total_memory / 2**30:.0f} GiB"},
@@ -478,7 +484,7 @@ def brief(res):
            "kernel": r["kernel"], "kernel_achieved": r["achieved"], "kernel_frac_of_peak": r["frac"], "bound": r["bound"]}
     if res["unit"] == "GB/s" and r["bound"] == "hbm":
         out["pct_hbm_peak"] = round(100.0 * res["value"] / HBM_PEAK_GBS, 2)
-    for k in ("single_step_us_median", "ms_mixed", "ms_decode_then_prefill", "ms_decode_alone", "ms_prefill_alone",
+    for k in ("single_step_us_median", "us_per_layer_plan_staged_once", "pct_hbm_peak_per_layer_plan_staged_once", "ms_mixed", "ms_decode_then_prefill", "ms_decode_alone", "ms_prefill_alone",
               "mixed_output_equals_separate_calls_bitwise"):
         if k in res["config"]:
             out[k] = res["config"][k]

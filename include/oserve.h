@@ -163,6 +163,28 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
                                          float scale, float* out, void* stream);
 
 /*
+ * The layers of a model.  A decode step runs every layer of the model on the same batch with
+ * the same context lengths (section 2, "Phases of LLM inference": one token per step through
+ * the whole model; section 5.2 speaks of the cache per layer), so the plan - and with it the
+ * work-item descriptors that the first kernel of oserve_paged_decode_attn writes into the
+ * workspace - is the same for all of them; only q, the K/V pools and out differ.
+ * oserve_plan_stage enqueues that first kernel alone, once per step; each layer then calls
+ * oserve_paged_decode_attn_staged, which enqueues only the split and merge kernels over the
+ * descriptors already in `workspace` (the partial results in the workspace are reused layer
+ * after layer, in stream order).  Results are bit-identical to oserve_paged_decode_attn.
+ *
+ * The staged call checks on the host that `workspace` is the one the plan was last staged
+ * into and that the plan has not been updated since (else OSERVE_ERR_PLAN_MISMATCH); all
+ * these calls must go to one stream, or to streams the caller orders.  Other arguments and
+ * errors: as oserve_paged_decode_attn.
+ */
+oserve_status_t oserve_plan_stage(oserve_plan_t* plan, void* workspace, size_t workspace_bytes, void* stream);
+oserve_status_t oserve_paged_decode_attn_staged(oserve_plan_t* plan, void* workspace, size_t workspace_bytes,
+                                                const void* q, const void* k_pages, const void* v_pages,
+                                                const int32_t* block_table, const int32_t* context_lens,
+                                                float scale, float* out, void* stream);
+
+/*
  * The same decode step for callers that cannot allocate device memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Identical to
  * oserve_paged_decode_attn except that the workspace is a fixed array of

@@ -50,6 +50,10 @@ def _load() -> ctypes.CDLL:
         getattr(lib, name).argtypes = [vp]
     lib.oserve_paged_decode_attn.restype = ctypes.c_int
     lib.oserve_paged_decode_attn.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
+    lib.oserve_plan_stage.restype = ctypes.c_int
+    lib.oserve_plan_stage.argtypes = [vp, vp, sz, vp]
+    lib.oserve_paged_decode_attn_staged.restype = ctypes.c_int
+    lib.oserve_paged_decode_attn_staged.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.oserve_paged_decode_attn_static.restype = ctypes.c_int
     lib.oserve_paged_decode_attn_static.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.oserve_static_workspace_bytes.restype = sz
@@ -278,6 +282,32 @@ def paged_decode_attn(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pa
     return out
 
 
+def plan_stage(plan: Plan, workspace: torch.Tensor, stream: torch.cuda.Stream | None = None) -> None:
+    """oserve_plan_stage: the plan's work-item descriptors written into `workspace`, once for all layers of a step."""
+    if workspace.device.type != "cuda" or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous tensor on the GPU")
+    s = torch.cuda.current_stream(workspace.device) if stream is None else stream
+    st = lib.oserve_plan_stage(plan.handle, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                               ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_plan_stage")
+
+
+def paged_decode_attn_staged(plan: Plan, workspace: torch.Tensor, q: torch.Tensor, k_pages: torch.Tensor,
+                             v_pages: torch.Tensor, block_table: torch.Tensor, context_lens: torch.Tensor,
+                             scale: float, out: torch.Tensor, stream: torch.cuda.Stream | None = None) -> torch.Tensor:
+    """oserve_paged_decode_attn_staged on torch tensors: one layer's split and merge kernels over staged descriptors."""
+    _check_decode_tensors(plan, q, k_pages, v_pages, block_table, context_lens, out, (workspace,))
+    s = torch.cuda.current_stream(q.device) if stream is None else stream
+    st = lib.oserve_paged_decode_attn_staged(plan.handle, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                             _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                             _ptr(context_lens), ctypes.c_float(scale), _ptr(out),
+                                             ctypes.c_void_p(s.cuda_stream))
+    if st != OK:
+        raise OserveError(st, "oserve_paged_decode_attn_staged")
+    return out
+
+
 def static_workspace_bytes() -> int:
     return lib.oserve_static_workspace_bytes()
 
@@ -318,6 +348,17 @@ class DecodeAttention:
             self.plan.update(inputs.context_lens_host)
         return paged_decode_attn(self.plan, self.workspace, inputs.q, inputs.k_pages, inputs.v_pages,
                                  inputs.block_table, inputs.context_lens, inputs.scale, self.out)
+
+    def stage(self, inputs, replan: bool = True) -> None:
+        """Once per decode step: re-plan and write the descriptors that every layer's `layer` call uses."""
+        if replan:
+            self.plan.update(inputs.context_lens_host)
+        plan_stage(self.plan, self.workspace)
+
+    def layer(self, inputs) -> torch.Tensor:
+        """One layer's attention over the staged descriptors."""
+        return paged_decode_attn_staged(self.plan, self.workspace, inputs.q, inputs.k_pages, inputs.v_pages,
+                                        inputs.block_table, inputs.context_lens, inputs.scale, self.out)
 
 
 class PrefillPlan:

@@ -28,6 +28,11 @@ struct oserve_plan {
     bool slot_used[OSERVE_PLAN_RING] = {};
     int next_slot = 0;
     oserve::KernelTimer<OSERVE_PLAN_RING> timer;   // optional split-kernel timing
+    int next_timer_slot = 0;
+    // oserve_plan_stage: which build of the plan was expanded into which workspace
+    uint64_t generation = 0;            // grows with every successful build
+    uint64_t staged_generation = 0;     // 0 = nothing staged
+    const void* staged_workspace = nullptr;
 };
 
 namespace {
@@ -98,13 +103,16 @@ oserve_status_t oserve_plan_create(const int32_t* context_lens_host, int32_t bat
         delete pl;
         return st;
     }
+    pl->generation = 1;
     *plan_out = pl;
     return OSERVE_OK;
 }
 
 oserve_status_t oserve_plan_update(oserve_plan_t* plan, const int32_t* context_lens_host, int32_t batch) {
     if (!plan || !context_lens_host) return OSERVE_ERR_NULL;
-    return plan->host.build(context_lens_host, batch);
+    const oserve_status_t st = plan->host.build(context_lens_host, batch);
+    if (st == OSERVE_OK) plan->generation += 1;   // descriptors staged for the previous build are stale now
+    return st;
 }
 
 void oserve_plan_destroy(oserve_plan_t* plan) {
@@ -156,33 +164,27 @@ size_t oserve_plan_workspace_bytes_max(const oserve_plan_t* plan) {
 
 namespace oserve {
 
-// The whole decode step on `stream`: records staged in the plan's next pinned slot, then the
-// expand, split and (if any request is split) merge kernels.  Allocates nothing.
-oserve_status_t decode_launch(oserve_plan_t* plan, void* workspace, size_t workspace_bytes, const void* q,
-                              const void* k_pages, const void* v_pages, const int32_t* block_table,
-                              const int32_t* context_lens, float scale, float* out, void* stream_v) {
-    if (!plan || !workspace || !q || !k_pages || !v_pages || !block_table || !context_lens || !out)
-        return OSERVE_ERR_NULL;
-    if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
+namespace {
+
+oserve_status_t check_workspace(const oserve_plan_t* plan, const void* workspace, size_t workspace_bytes,
+                                WorkspaceLayout* lay) {
+    const SplitPlan& hp = plan->host;
+    *lay = hp.layout(hp.num_items, hp.num_row_groups, hp.batch);
+    if (workspace_bytes < lay->total || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return OSERVE_ERR_WORKSPACE;
+    return OSERVE_OK;
+}
+
+// Records staged in the plan's next pinned slot, then the expand kernel that turns them into the
+// work-item descriptors and request records of `workspace`.
+oserve_status_t enqueue_expand(oserve_plan_t* plan, const WorkspaceLayout& lay, void* workspace, hipStream_t stream) {
     const SplitPlan& hp = plan->host;
     const int64_t num_runs = static_cast<int64_t>(hp.records.size());
-    const WorkspaceLayout lay = hp.layout(hp.num_items, hp.num_row_groups, hp.batch);
-    if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-        return OSERVE_ERR_WORKSPACE;
-    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pages) |
-         reinterpret_cast<uintptr_t>(v_pages) | reinterpret_cast<uintptr_t>(out)) & 15u)
-        return OSERVE_ERR_ALIGNMENT;
-
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    DeviceGuard guard(plan->device_id);
-    if (!guard.ok) return OSERVE_ERR_DEVICE;
-
-    // stage the records in the next pinned slot (waits only if that slot's last upload is still pending)
+    // waits only if that slot's last upload is still pending
     const int slot = plan->next_slot;
     plan->next_slot = (slot + 1) % OSERVE_PLAN_RING;
     if (plan->slot_used[slot] && hipEventSynchronize(plan->upload_done[slot]) != hipSuccess)
         return OSERVE_ERR_DEVICE;
-    if (plan->timer.enabled && !plan->timer.collect(slot)) return OSERVE_ERR_DEVICE;
     // slot layout: [run records][request info]; both 16-byte aligned
     const size_t slot_off = static_cast<size_t>(slot) * plan->staging_slot_bytes;
     const size_t info_off = sizeof(RunRecord) * static_cast<size_t>(num_runs);
@@ -200,10 +202,23 @@ oserve_status_t decode_launch(oserve_plan_t* plan, void* workspace, size_t works
     ep.kv_heads_magic = static_cast<uint32_t>((1ull << 32) / static_cast<uint32_t>(hp.geo.num_kv_heads)) + 1u;
     if (launch_expand(ep, stream, plan->upload_done[slot]) != hipSuccess) return OSERVE_ERR_DEVICE;
     plan->slot_used[slot] = true;
+    return OSERVE_OK;
+}
+
+// The split kernel and (if any request is split) the merge kernel over descriptors that are in `workspace`.
+oserve_status_t enqueue_split_and_merge(oserve_plan_t* plan, const WorkspaceLayout& lay, void* workspace,
+                                        const void* q, const void* k_pages, const void* v_pages,
+                                        const int32_t* block_table, const int32_t* context_lens, float scale,
+                                        float* out, hipStream_t stream) {
+    const SplitPlan& hp = plan->host;
+    char* ws = static_cast<char*>(workspace);
+    const int tslot = plan->next_timer_slot;
+    plan->next_timer_slot = (tslot + 1) % OSERVE_PLAN_RING;
+    if (plan->timer.enabled && !plan->timer.collect(tslot)) return OSERVE_ERR_DEVICE;
 
     SplitParams sp{};
-    sp.items = ep.items;
-    sp.req_info = ep.req_info;
+    sp.items = reinterpret_cast<const ItemDesc*>(ws + lay.items_off);
+    sp.req_info = reinterpret_cast<const RequestInfo*>(ws + lay.req_info_off);
     sp.q = static_cast<const uint16_t*>(q);
     sp.k_pages = static_cast<const uint16_t*>(k_pages);
     sp.v_pages = static_cast<const uint16_t*>(v_pages);
@@ -219,13 +234,13 @@ oserve_status_t decode_launch(oserve_plan_t* plan, void* workspace, size_t works
     sp.max_pages_per_seq = hp.geo.max_pages_per_seq;
     sp.tile_shift = hp.geo.page_size == 64 ? 2 : hp.geo.page_size == 32 ? 1 : 0;
 
-    if (launch_split(sp, hp.geo.head_dim, hp.num_items, stream, plan->timer.begin_of(slot),
-                     plan->timer.end_of(slot)) != hipSuccess)
+    if (launch_split(sp, hp.geo.head_dim, hp.num_items, stream, plan->timer.begin_of(tslot),
+                     plan->timer.end_of(tslot)) != hipSuccess)
         return OSERVE_ERR_DEVICE;
-    plan->timer.mark(slot);
+    plan->timer.mark(tslot);
 
     MergeParams mp{};
-    mp.req_info = reinterpret_cast<const RequestInfo*>(ws + lay.req_info_off);
+    mp.req_info = sp.req_info;
     mp.partial_o = sp.partial_o;
     mp.partial_ml = sp.partial_ml;
     mp.out = out;
@@ -234,6 +249,34 @@ oserve_status_t decode_launch(oserve_plan_t* plan, void* workspace, size_t works
         if (launch_merge(mp, hp.geo.head_dim, hp.batch, stream) != hipSuccess) return OSERVE_ERR_DEVICE;
     }
     return OSERVE_OK;
+}
+
+bool misaligned(const void* q, const void* k_pages, const void* v_pages, const void* out) {
+    return ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pages) |
+             reinterpret_cast<uintptr_t>(v_pages) | reinterpret_cast<uintptr_t>(out)) & 15u) != 0;
+}
+
+}  // namespace
+
+// The whole decode step on `stream`: the expand, split and (if any request is split) merge kernels.
+// Allocates nothing.
+oserve_status_t decode_launch(oserve_plan_t* plan, void* workspace, size_t workspace_bytes, const void* q,
+                              const void* k_pages, const void* v_pages, const int32_t* block_table,
+                              const int32_t* context_lens, float scale, float* out, void* stream_v) {
+    if (!plan || !workspace || !q || !k_pages || !v_pages || !block_table || !context_lens || !out)
+        return OSERVE_ERR_NULL;
+    if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
+    WorkspaceLayout lay;
+    oserve_status_t st = check_workspace(plan, workspace, workspace_bytes, &lay);
+    if (st != OSERVE_OK) return st;
+    if (misaligned(q, k_pages, v_pages, out)) return OSERVE_ERR_ALIGNMENT;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    DeviceGuard guard(plan->device_id);
+    if (!guard.ok) return OSERVE_ERR_DEVICE;
+    if (workspace == plan->staged_workspace) plan->staged_generation = 0;   // re-expanded below: the same content, but staged no longer
+    st = enqueue_expand(plan, lay, workspace, stream);
+    if (st != OSERVE_OK) return st;
+    return enqueue_split_and_merge(plan, lay, workspace, q, k_pages, v_pages, block_table, context_lens, scale, out, stream);
 }
 
 size_t decode_workspace_bytes(const oserve_plan_t* plan) { return oserve_plan_workspace_bytes(plan); }
@@ -249,6 +292,42 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace, s
                                          float scale, float* out, void* stream) {
     return oserve::decode_launch(plan, workspace, workspace_bytes, q, k_pages, v_pages, block_table,
                                  context_lens, scale, out, stream);
+}
+
+oserve_status_t oserve_plan_stage(oserve_plan_t* plan, void* workspace, size_t workspace_bytes, void* stream_v) {
+    if (!plan || !workspace) return OSERVE_ERR_NULL;
+    if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
+    oserve::WorkspaceLayout lay;
+    const oserve_status_t st = oserve::check_workspace(plan, workspace, workspace_bytes, &lay);
+    if (st != OSERVE_OK) return st;
+    oserve::DeviceGuard guard(plan->device_id);
+    if (!guard.ok) return OSERVE_ERR_DEVICE;
+    plan->staged_generation = 0;
+    const oserve_status_t se = oserve::enqueue_expand(plan, lay, workspace, static_cast<hipStream_t>(stream_v));
+    if (se != OSERVE_OK) return se;
+    plan->staged_generation = plan->generation;
+    plan->staged_workspace = workspace;
+    return OSERVE_OK;
+}
+
+oserve_status_t oserve_paged_decode_attn_staged(oserve_plan_t* plan, void* workspace, size_t workspace_bytes,
+                                                const void* q, const void* k_pages, const void* v_pages,
+                                                const int32_t* block_table, const int32_t* context_lens,
+                                                float scale, float* out, void* stream_v) {
+    if (!plan || !workspace || !q || !k_pages || !v_pages || !block_table || !context_lens || !out)
+        return OSERVE_ERR_NULL;
+    if (plan->device_id < 0) return OSERVE_ERR_PLAN_MISMATCH;
+    // the descriptors in `workspace` must be those of the plan as it is now
+    if (plan->staged_generation == 0 || plan->staged_generation != plan->generation || plan->staged_workspace != workspace)
+        return OSERVE_ERR_PLAN_MISMATCH;
+    oserve::WorkspaceLayout lay;
+    const oserve_status_t st = oserve::check_workspace(plan, workspace, workspace_bytes, &lay);
+    if (st != OSERVE_OK) return st;
+    if (oserve::misaligned(q, k_pages, v_pages, out)) return OSERVE_ERR_ALIGNMENT;
+    oserve::DeviceGuard guard(plan->device_id);
+    if (!guard.ok) return OSERVE_ERR_DEVICE;
+    return oserve::enqueue_split_and_merge(plan, lay, workspace, q, k_pages, v_pages, block_table, context_lens,
+                                           scale, out, static_cast<hipStream_t>(stream_v));
 }
 
 oserve_status_t oserve_plan_enable_timing(oserve_plan_t* plan, int32_t enable) {

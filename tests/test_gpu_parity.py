@@ -230,6 +230,44 @@ def test_many_launches_wrap_the_staging_ring():
     gh.assert_parity(out, gh.oracle_attention(cpu), "ring")
 
 
+def test_layers_over_one_staged_plan():
+    """The descriptors staged once serve every layer of a step: two "layers" (different q, K/V pools and page
+    placement over the same lengths) through oserve_paged_decode_attn_staged equal the ordinary call bit for bit
+    and the oracle within the bar; a stale stage is refused."""
+    from paper_2602_12151_amd import binding
+    lens = np.array([300, 5000, 64, 1, 2047, 17], dtype=np.int32)
+    w = wl.WORKLOADS[1]
+    cpus = [wl.make_inputs(w, device="cpu", seed=70 + layer, lens=lens) for layer in range(2)]
+    devs = [gh.to_device(c) for c in cpus]
+    op = binding.DecodeAttention(devs[0])
+    assert op.plan.num_work_items > len(lens) * w.num_kv_heads        # some request is split
+    plain = [op.step(d, replan=False).clone() for d in devs]
+    torch.cuda.synchronize()
+    op.stage(devs[0])
+    for _ in range(3):                                                 # the stage survives many layers
+        for layer, d in enumerate(devs):
+            out = op.layer(d)
+            torch.cuda.synchronize()
+            assert torch.equal(out, plain[layer]), layer
+    for layer, c in enumerate(cpus):
+        gh.assert_parity(plain[layer], gh.oracle_attention(c), f"layer {layer}")
+    # a different workspace, an updated plan, or the ordinary call on the same workspace: staged no longer
+    other = torch.empty_like(op.workspace)
+    with pytest.raises(binding.OserveError) as e:
+        binding.paged_decode_attn_staged(op.plan, other, devs[0].q, devs[0].k_pages, devs[0].v_pages,
+                                         devs[0].block_table, devs[0].context_lens, devs[0].scale, op.out)
+    assert e.value.status == binding.ERR_PLAN_MISMATCH
+    op.plan.update(devs[0].context_lens_host)
+    with pytest.raises(binding.OserveError):
+        op.layer(devs[0])
+    op.stage(devs[0], replan=False)
+    assert torch.equal(op.layer(devs[1]), plain[1])
+    op.step(devs[0], replan=False)
+    with pytest.raises(binding.OserveError):
+        op.layer(devs[0])
+    torch.cuda.synchronize()
+
+
 # ----------------------------------------------------------------------------
 # full-size workloads in the launch configuration bench.py times (automatic plan): every element of
 # `out` against the oracle (the oracle needs a few seconds per workload)
