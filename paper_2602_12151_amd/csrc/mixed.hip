@@ -44,7 +44,8 @@ constexpr int kMixedThreads = 64 * kMixedWaves;
 // (the prefill code loses its software pipelining: every LDS read waits for the one before); as
 // functions each is compiled like the kernel it also exists as.  The loop over a queue's items is
 // inside the function because a function saves the registers it must preserve to scratch memory on
-// entry and reloads them on exit: per item that was 128 MB of writes per launch and 3 % of its time.
+// entry and reloads them on exit (30 KB per wavefront for the prefill function): called per item
+// that was 3 % of the launch's time; called once per phase it is 80 MB of scratch traffic per launch.
 // The functions read their parameters from the kernel-argument segment, in the constant address
 // space: scalar loads into scalar registers, as in a kernel.  (Handed over by reference the
 // parameters would be vector-memory loads where they are used, and waiting for one of those also
