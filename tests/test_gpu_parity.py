@@ -268,6 +268,42 @@ def test_layers_over_one_staged_plan():
     torch.cuda.synchronize()
 
 
+def test_staged_layers_in_a_hip_graph():
+    """The staged call enqueues kernels only (no copy, no event, no wait), so a serving loop can capture the layers
+    of a step into a HIP graph: every replay, with eager work in between, gives the eager result bit for bit."""
+    from paper_2602_12151_amd import binding
+    lens = np.array([700, 33, 4000, 1, 129], dtype=np.int32)
+    w = wl.WORKLOADS[1]
+    devs = [gh.to_device(wl.make_inputs(w, device="cpu", seed=80 + layer, lens=lens)) for layer in range(2)]
+    op = binding.DecodeAttention(devs[0])
+    eager = [op.step(d, replan=False).clone() for d in devs]
+    outs = [torch.empty_like(eager[0]) for _ in devs]
+    op.stage(devs[0], replan=False)
+    torch.cuda.synchronize()
+
+    def layers():
+        for _ in range(2):
+            for d, o in zip(devs, outs):
+                binding.paged_decode_attn_staged(op.plan, op.workspace, d.q, d.k_pages, d.v_pages, d.block_table,
+                                                 d.context_lens, d.scale, o)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        layers()
+    for replay in range(4):
+        for o in outs:
+            o.fill_(float("nan"))                       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for layer in range(2):
+            assert torch.equal(outs[layer], eager[layer]), (replay, layer)
+    layers()                                            # and the plan still launches eagerly afterwards
+    torch.cuda.synchronize()
+    assert torch.equal(outs[1], eager[1])
+
+
 # ----------------------------------------------------------------------------
 # full-size workloads in the launch configuration bench.py times (automatic plan): every element of
 # `out` against the oracle (the oracle needs a few seconds per workload)
