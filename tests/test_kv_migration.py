@@ -135,3 +135,57 @@ def test_gpu_migrated_requests_attend_identically_on_the_target():
     out_dst, _ = gh.gpu_attention(dst, split_tokens=1024)
     out_src, _ = gh.gpu_attention(src, split_tokens=1024)
     assert torch.equal(out_dst, out_src[torch.from_numpy(rows).long().cuda()])
+
+
+@pytest.mark.gpu
+def test_gpu_full_size_chunk_is_bit_exact():
+    """The chunk bench.py times (the long requests of the heterogeneous mix, 6.4 GB of K+V, a target pool holding
+    half the kv heads at an offset): every migrated page equals its source bit for bit, checked request by request
+    with plain tensor indexing, and the oracle confirms a sampled request."""
+    w = wl.WORKLOADS[3]
+    print("generating the heterogeneous mix", flush=True)
+    inp = wl.make_inputs(w, device="cuda")
+    lens = inp.context_lens_host
+    rows = np.nonzero(lens >= 8192)[0].astype(np.int32)
+    mlens = lens[rows]
+    m = binding.KvMigration(mlens, rows, w.page_size)
+    n = m.num_pages
+    head_begin, heads = 2, 4                                   # the target GPU takes kv heads 2..5 of 8 ...
+    stage_shape = (n, heads, w.page_size, w.head_dim)
+    k_stage = torch.empty(stage_shape, dtype=torch.bfloat16, device="cuda")
+    v_stage = torch.empty_like(k_stage)
+    need = wl.pages_needed(mlens, w.page_size)
+    pool_pages = int(np.ceil(1.15 * n))
+    perm = wl.CounterRng(991).permutation(pool_pages)[:n]
+    off = np.concatenate([[0], np.cumsum(need)])
+    tt = np.full((len(rows), int(need.max())), -1, dtype=np.int32)
+    for r in range(len(rows)):
+        tt[r, : need[r]] = perm[off[r]: off[r + 1]]
+    tt_dev = torch.from_numpy(tt).cuda()
+    dst_heads, dst_begin = 6, 1                                # ... and holds them as heads 1..4 of 6 per page
+    k_dst = torch.zeros((pool_pages, dst_heads, w.page_size, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_dst = torch.zeros_like(k_dst)
+    print(f"gather + scatter of {n} pages", flush=True)
+    m.gather(inp.k_pages, inp.v_pages, inp.block_table, head_begin, heads, k_stage, v_stage)
+    m.scatter(k_stage, v_stage, tt_dev, dst_begin, k_dst, v_dst)
+    torch.cuda.synchronize()
+    for r, row in enumerate(rows):
+        src = inp.block_table[int(row), : int(need[r])].long()
+        dst = tt_dev[r, : int(need[r])].long()
+        for pool, stage, target in ((inp.k_pages, k_stage, k_dst), (inp.v_pages, v_stage, v_dst)):
+            want = pool[src][:, head_begin:head_begin + heads].view(torch.int16)
+            assert torch.equal(stage[int(off[r]): int(off[r + 1])].view(torch.int16), want), r
+            assert torch.equal(target[dst][:, dst_begin:dst_begin + heads].view(torch.int16), want), r
+    # heads of the target pool outside the copied range, and pages no request names, were not written
+    assert int(k_dst[:, :dst_begin].view(torch.int16).abs().max()) == 0
+    assert int(v_dst[:, dst_begin + heads:].view(torch.int16).abs().max()) == 0
+    unused = np.setdiff1d(np.arange(pool_pages), perm)
+    assert int(k_dst[torch.from_numpy(unused).cuda()].view(torch.int16).abs().max()) == 0
+    # the oracle on one sampled request (its pages copied to the host)
+    r = len(rows) // 2
+    src = inp.block_table[int(rows[r]), : int(need[r])].long()
+    small_pool_k = inp.k_pages[src].view(torch.int16).cpu().numpy().view(np.uint16)
+    table = np.arange(int(need[r]), dtype=np.int32)[None, :]
+    ref = mo.gather(small_pool_k, table, [0], [int(mlens[r])], head_begin=head_begin, num_heads=heads)
+    got = k_stage[int(off[r]): int(off[r + 1])].view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, ref)
