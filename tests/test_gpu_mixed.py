@@ -122,6 +122,55 @@ def test_serving_shaped_batch_whole_tensor():
     print(f"serving-shaped: {plan.counts}, whole {err}, parts {parts}")
 
 
+def test_bench_workload_sampled():
+    """The batch `bench.py --mixed` times (the 256 decode requests of the heterogeneous mix + 8 chunks of 512
+    tokens), at full size and in its launch configuration: sampled decode rows and sampled prefill rows against
+    the oracle, each kind to its own bar, and every row finite."""
+    w, lens, qlens = wl.mixed_workload()
+    inp = wl.make_inputs(w, device="cuda", seed=w.seed, lens=lens)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 1)
+    q = torch.randn(int(qlens.sum()), w.num_q_heads, w.head_dim, generator=gen, device="cuda").to(torch.bfloat16)
+    out = torch.full(q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    plan = binding.MixedPlan(lens, qlens, w.num_q_heads, w.num_kv_heads, w.head_dim, w.page_size,
+                             inp.block_table.shape[1], 0)
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    binding.paged_mixed_attn(plan, ws, q, inp.k_pages, inp.v_pages, inp.block_table, inp.context_lens, w.scale, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    rng = np.random.default_rng(4242)
+    row0 = np.concatenate([[0], np.cumsum(qlens)])
+    decode = np.nonzero(qlens == 1)[0]
+    chunks = np.nonzero(qlens > 1)[0]
+    picks = {"decode": [], "prefill": []}
+    for b in (int(decode[0]), int(decode[-1]), int(decode[np.argmax(lens[decode])]), int(decode[np.argmin(lens[decode])])):
+        picks["decode"].append((b, 0, int(rng.integers(0, w.num_q_heads))))
+    for _ in range(20):
+        picks["decode"].append((int(rng.choice(decode)), 0, int(rng.integers(0, w.num_q_heads))))
+    for b in (int(chunks[0]), int(chunks[-1])):
+        for i in (0, 31, 32, 33, 255, 510, 511):
+            picks["prefill"].append((b, i, int(rng.integers(0, w.num_q_heads))))
+    for _ in range(12):
+        b = int(rng.choice(chunks))
+        picks["prefill"].append((b, int(rng.integers(0, qlens[b])), int(rng.integers(0, w.num_q_heads))))
+    for kind, rows in picks.items():
+        got, ref = [], []
+        for b, i, h in rows:
+            row = int(row0[b]) + i
+            visible = int(lens[b] - qlens[b]) + i + 1
+            n = (visible + w.page_size - 1) // w.page_size
+            ids = inp.block_table[b, :n].long()
+            j = h // w.group
+            ref.append(oracle.paged_decode_attn(q[row:row + 1, h:h + 1].cpu(), inp.k_pages[ids, j:j + 1].cpu(),
+                                                inp.v_pages[ids, j:j + 1].cpu(), np.arange(n, dtype=np.int32)[None, :],
+                                                np.array([visible], dtype=np.int32), inp.scale)[0, 0])
+            got.append(out[row, h])
+        err = gh.assert_parity(torch.stack(got), np.stack(ref), f"mixed bench workload, {kind} rows")
+        print(f"mixed bench workload: {len(rows)} {kind} rows, max_abs {err[0]:.2e}, rel_l2 {err[1]:.2e}", flush=True)
+        if kind == "decode":
+            assert err[1] < 2e-5          # the decode items carry the weights as hi + lo halves
+
+
 def test_update_and_rerun_is_bit_identical():
     case = make_case([700, 90, 3000, 50], [200, 90, 1, 1], 32, 8, seed=9)
     w, cpu, q, lens, qlens = case
