@@ -154,6 +154,21 @@ def test_plan_without_device_cannot_launch():
     assert st == binding.ERR_NULL
 
 
+def test_staged_calls_check_their_arguments_on_the_host():
+    """oserve_plan_stage / oserve_paged_decode_attn_staged refuse null pointers and a plan without a device before
+    anything is enqueued (the checks that need no GPU)."""
+    import ctypes
+    plan = make_plan([100, 200])
+    p = ctypes.c_void_p(256)
+    assert binding.lib.oserve_plan_stage(plan.handle, None, 1 << 20, None) == binding.ERR_NULL
+    assert binding.lib.oserve_plan_stage(None, p, 1 << 20, None) == binding.ERR_NULL
+    assert binding.lib.oserve_plan_stage(plan.handle, p, 1 << 20, None) == binding.ERR_PLAN_MISMATCH
+    st = binding.lib.oserve_paged_decode_attn_staged(plan.handle, p, 1 << 20, p, p, p, p, p, ctypes.c_float(1.0), p, None)
+    assert st == binding.ERR_PLAN_MISMATCH
+    st = binding.lib.oserve_paged_decode_attn_staged(plan.handle, p, 1 << 20, None, p, p, p, p, ctypes.c_float(1.0), p, None)
+    assert st == binding.ERR_NULL
+
+
 def test_library_exports_every_declared_symbol():
     import re, os
     hdr = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "oserve.h")).read()
