@@ -172,6 +172,12 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
  * oserve_paged_decode_attn_staged, which enqueues only the split and merge kernels over the
  * descriptors already in `workspace` (the partial results in the workspace are reused layer
  * after layer, in stream order).  Results are bit-identical to oserve_paged_decode_attn.
+ * The staged call enqueues kernels and nothing else (no copy, no event, no wait), so the
+ * layers of a step may be captured into a HIP graph and replayed.  The calls that stage
+ * records (oserve_plan_stage, oserve_paged_decode_attn, oserve_paged_decode_attn_static,
+ * oserve_paged_mixed_attn, oserve_paged_prefill_attn) copy them into a pinned slot when they
+ * are called and attach an event to their first kernel: call those eagerly, not under capture
+ * (a replay would read whatever the slot holds by then).
  *
  * The staged call checks on the host that `workspace` is the one the plan was last staged
  * into and that the plan has not been updated since (else OSERVE_ERR_PLAN_MISMATCH); all
