@@ -191,8 +191,9 @@ oserve_status_t oserve_paged_decode_attn_staged(oserve_plan_t* plan, void* works
                                                 float scale, float* out, void* stream);
 
 /*
- * The same decode step for callers that cannot allocate device memory: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Identical to
+ * The same decode step for callers that cannot allocate device memory: code that runs while a
+ * HIP graph capture is in progress in the process (hipMalloc is not allowed then), tight
+ * serving loops, harnesses that forbid hipMalloc.  Identical to
  * oserve_paged_decode_attn except that the workspace is a fixed array of
  * OSERVE_STATIC_WORKSPACE_BYTES bytes that the library holds in the memory of every GPU it is
  * loaded on, from load until the process ends.  The call itself allocates and frees nothing (no
