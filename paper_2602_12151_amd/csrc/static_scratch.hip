@@ -1,5 +1,5 @@
-// The decode step for callers that cannot allocate device memory (code under HIP graph capture,
-// tight serving loops, harnesses that forbid hipMalloc): the same launch sequence as
+// The decode step for callers that cannot allocate device memory (code that runs while a HIP graph
+// capture is in progress, tight serving loops, harnesses that forbid hipMalloc): the same launch sequence as
 // oserve_paged_decode_attn, with the workspace taken from a fixed array in device memory instead
 // of from the caller.
 //
