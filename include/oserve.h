@@ -33,6 +33,8 @@
  *     slots for its records, so the (OSERVE_PLAN_RING+1)-th launch of a plan
  *     waits until the oldest launch's record copy has run on the device.
  *   - Every function returns a status code; nothing throws or aborts.
+ *   - Objects are not synchronised: one plan (or migration) object must not be used by two
+ *     threads at the same time; different objects are independent.
  *   - hipStream_t is passed as void* (null = the default stream).
  */
 #ifndef OSERVE_H_
