@@ -18,8 +18,6 @@ constexpr int kExpandLanes = 16;    // lanes that expand one run together
 __global__ __launch_bounds__(kExpandThreads) void expand_plan_kernel(const ExpandParams p) {
     __shared__ uint4 staged[kExpandChunk * 2];
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
     {
         const uint4* src = reinterpret_cast<const uint4*>(p.req_info_host);
         uint4* dst = reinterpret_cast<uint4*>(p.req_info);
