@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboserve.so")
 SOURCES = ["kernels.hip", "prefill.hip", "migrate.hip", "static_scratch.hip", "mixed.hip", "api.cpp", "api_prefill.cpp", "api_migrate.cpp", "api_mixed.cpp", "plan.cpp", "prefill_plan.cpp", "planner.cpp"]
-HEADERS = ["kernels.h", "plan.h", "host_util.h", "decode_launch.h", "prefill_plan.h", "decode_body.h", "prefill_body.h", os.path.join(ROOT, "include", "oserve.h")]
+HEADERS = ["kernels.h", "plan.h", "host_util.h", "decode_launch.h", "prefill_plan.h", "decode_body.h", "prefill_body.h", "launch_util.h", os.path.join(ROOT, "include", "oserve.h")]
 
 
 def hipcc_command(out: str = LIB) -> list:

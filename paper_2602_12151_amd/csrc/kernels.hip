@@ -2,6 +2,7 @@
 // split kernel (one wavefront per work item; the work itself is in decode_body.h, shared with the
 // mixed prefill + decode kernel) and the log-sum-exp merge of the splits.
 #include "decode_body.h"
+#include "launch_util.h"
 
 namespace oserve {
 namespace {
@@ -117,31 +118,24 @@ hipError_t launch_split(const SplitParams& p, int head_dim, int num_items, hipSt
                         hipEvent_t start, hipEvent_t stop) {
     if (num_items <= 0) return hipSuccess;
     if (head_dim == 128)
-        hipExtLaunchKernelGGL((paged_decode_split_kernel<128, kPagesInFlight, kWavesPerSimd>), dim3(num_items), dim3(64),
-                              0, stream, start, stop, 0, p);
-    else if (head_dim == 64)
-        hipExtLaunchKernelGGL((paged_decode_split_kernel<64, kPagesInFlight, kWavesPerSimd>), dim3(num_items), dim3(64),
-                              0, stream, start, stop, 0, p);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+        return launch_kernel(paged_decode_split_kernel<128, kPagesInFlight, kWavesPerSimd>, dim3(num_items), dim3(64),
+                             stream, start, stop, p);
+    if (head_dim == 64)
+        return launch_kernel(paged_decode_split_kernel<64, kPagesInFlight, kWavesPerSimd>, dim3(num_items), dim3(64),
+                             stream, start, stop, p);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_expand(const ExpandParams& p, hipStream_t stream, hipEvent_t done) {
-    hipExtLaunchKernelGGL(expand_plan_kernel, dim3(1), dim3(kExpandThreads), 0, stream, nullptr, done, 0, p);
-    return hipGetLastError();
+    return launch_kernel(expand_plan_kernel, dim3(1), dim3(kExpandThreads), stream, nullptr, done, p);
 }
 
 hipError_t launch_merge(const MergeParams& p, int head_dim, int batch, hipStream_t stream) {
     const int grid = batch * p.num_q_heads;
     if (grid <= 0) return hipSuccess;
-    if (head_dim == 128)
-        hipLaunchKernelGGL((paged_decode_merge_kernel<128>), dim3(grid), dim3(64), 0, stream, p);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL((paged_decode_merge_kernel<64>), dim3(grid), dim3(64), 0, stream, p);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (head_dim == 128) return launch_kernel(paged_decode_merge_kernel<128>, dim3(grid), dim3(64), stream, nullptr, nullptr, p);
+    if (head_dim == 64) return launch_kernel(paged_decode_merge_kernel<64>, dim3(grid), dim3(64), stream, nullptr, nullptr, p);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace oserve

@@ -16,6 +16,7 @@
 #include <cstdint>
 
 #include "kernels.h"
+#include "launch_util.h"
 
 namespace oserve {
 namespace {
@@ -61,11 +62,8 @@ hipError_t launch_kv_migrate(const MigrateParams& p, bool gather, hipStream_t st
     // chunks beyond the grid limit
     const int64_t cap = int64_t{1} << 30;
     const dim3 grid(static_cast<unsigned>(p.num_pages < cap ? p.num_pages : cap), 2);
-    if (gather)
-        hipExtLaunchKernelGGL((kv_migrate_kernel<true>), grid, dim3(kMigrateThreads), 0, stream, start, stop, 0, p);
-    else
-        hipExtLaunchKernelGGL((kv_migrate_kernel<false>), grid, dim3(kMigrateThreads), 0, stream, start, stop, 0, p);
-    return hipGetLastError();
+    if (gather) return launch_kernel(kv_migrate_kernel<true>, grid, dim3(kMigrateThreads), stream, start, stop, p);
+    return launch_kernel(kv_migrate_kernel<false>, grid, dim3(kMigrateThreads), stream, start, stop, p);
 }
 
 }  // namespace oserve

@@ -32,6 +32,7 @@
 // change the item's result, so the output is the same bit for bit from run to run.
 #include "decode_body.h"
 #include "prefill_body.h"
+#include "launch_util.h"
 
 namespace oserve {
 namespace {
@@ -146,13 +147,9 @@ void paged_mixed_kernel(const MixedParams p) {
 hipError_t launch_mixed(const MixedParams& p, int head_dim, int num_workgroups, hipStream_t stream,
                         hipEvent_t start, hipEvent_t stop) {
     if (num_workgroups <= 0) return hipSuccess;
-    if (head_dim == 128)
-        hipExtLaunchKernelGGL((paged_mixed_kernel<128>), dim3(num_workgroups), dim3(kMixedThreads), 0, stream, start, stop, 0, p);
-    else if (head_dim == 64)
-        hipExtLaunchKernelGGL((paged_mixed_kernel<64>), dim3(num_workgroups), dim3(kMixedThreads), 0, stream, start, stop, 0, p);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (head_dim == 128) return launch_kernel(paged_mixed_kernel<128>, dim3(num_workgroups), dim3(kMixedThreads), stream, start, stop, p);
+    if (head_dim == 64) return launch_kernel(paged_mixed_kernel<64>, dim3(num_workgroups), dim3(kMixedThreads), stream, start, stop, p);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace oserve

@@ -1,6 +1,7 @@
 // gfx950 kernel: causal chunked-prefill attention over the paged KV cache (one workgroup per work
 // item; the work itself is in prefill_body.h, shared with the mixed prefill + decode kernel).
 #include "prefill_body.h"
+#include "launch_util.h"
 
 namespace oserve {
 namespace {
@@ -19,15 +20,10 @@ void paged_prefill_kernel(const PrefillParams p) {
 hipError_t launch_prefill(const PrefillParams& p, int head_dim, int num_items, hipStream_t stream,
                           hipEvent_t start, hipEvent_t stop) {
     if (num_items <= 0) return hipSuccess;
-    if (head_dim == 128)
-        hipExtLaunchKernelGGL((paged_prefill_kernel<128>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
-                              start, stop, 0, p);
-    else if (head_dim == 64)
-        hipExtLaunchKernelGGL((paged_prefill_kernel<64>), dim3(num_items), dim3(prefill_detail::kPrefillThreads), 0, stream,
-                              start, stop, 0, p);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+    const dim3 block(prefill_detail::kPrefillThreads);
+    if (head_dim == 128) return launch_kernel(paged_prefill_kernel<128>, dim3(num_items), block, stream, start, stop, p);
+    if (head_dim == 64) return launch_kernel(paged_prefill_kernel<64>, dim3(num_items), block, stream, start, stop, p);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace oserve

@@ -289,8 +289,14 @@ def test_staged_layers_in_a_hip_graph():
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.graph(graph, stream=side):
-        layers()
+    import gc
+    gc.collect()
+    gc.disable()            # a plan object finalised during the capture would free pinned memory, which a capture forbids
+    try:
+        with torch.cuda.graph(graph, stream=side):
+            layers()
+    finally:
+        gc.enable()
     for replay in range(4):
         for o in outs:
             o.fill_(float("nan"))                       # eager work between the replays
