@@ -180,7 +180,8 @@ oserve_status_t oserve_paged_decode_attn(oserve_plan_t* plan, void* workspace,
  * oserve_paged_mixed_attn, oserve_paged_prefill_attn) copy them into a pinned slot when they
  * are called and attach an event to their first kernel: call those eagerly, not under capture
  * (a replay would read whatever the slot holds by then).
- * The create and destroy calls allocate and free pinned memory and are not for capture either.
+ * The create and destroy calls allocate and free pinned memory and are not for capture either,
+ * and the optional kernel timing (oserve_plan_enable_timing) must be off while capturing.
  *
  * The staged call checks on the host that `workspace` is the one the plan was last staged
  * into and that the plan has not been updated since (else OSERVE_ERR_PLAN_MISMATCH); all
