@@ -59,3 +59,23 @@ def test_recorded_traffic_belongs_to_the_current_sources():
     w = wl.WORKLOADS[rec["config"]]
     algorithmic = wl.kv_bytes(wl.context_lens(w), w.num_kv_heads, w.head_dim)
     assert algorithmic <= rec["bytes"] <= 1.05 * algorithmic
+
+
+def test_header_is_plain_c():
+    """include/oserve.h is a C header: it compiles as C99 without warnings, and a C program can name every
+    entry point it declares (link-time check against the built library)."""
+    import re, tempfile
+    header = open(os.path.join(ROOT, "include", "oserve.h")).read()
+    names = sorted(set(re.findall(r"\b(oserve_[a-z0-9_]+)\s*\(", header)))
+    assert len(names) > 40
+    body = "".join(f"    sink += (unsigned long)(void*)&{n};\n" for n in names)
+    src = '#include "oserve.h"\nint main(void) {\n    unsigned long sink = 0;\n' + body + "    return sink == 1;\n}\n"
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "use_header.c")
+        open(c, "w").write(src)
+        lib_dir = os.path.join(ROOT, "paper_2602_12151_amd")
+        proc = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror",
+                               "-I" + os.path.join(ROOT, "include"), c, "-o", os.path.join(d, "use_header"),
+                               "-L" + lib_dir, "-l:liboserve.so", "-Wl,--unresolved-symbols=ignore-in-shared-libs"],
+                              stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+        assert proc.returncode == 0, proc.stdout
